@@ -1,0 +1,254 @@
+"""CPU oracle for the V:N:M sparse linear path (TEST INFRASTRUCTURE ONLY).
+
+This module is the slow, plain definition the GPU library is checked against.
+It is imported only by the tests, by the smoke check and by the benchmark's
+``cpu_baseline`` leg.  It shares no code with the HIP path and must never be
+imported by the product package.
+
+Everything here follows the paper's own wording of the method:
+
+* Section 3 ("Pruning of V:N:M sparsity"): the three pruning steps
+  (importance score, column pruning per V x M block by column L1 norm,
+  2:4 inside the four surviving columns of every row).
+* Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
+  input dimension is a multiple of M and the output dimension a multiple of V.
+* Appendix A: the compressed triple -- the compact kept values (A_n), the four
+  kept column indices of every block (A_i1), and for every kept value its
+  position among the four surviving columns (A_i2).
+
+Readings taken where the paper is silent (each is listed in the design notes):
+ties are broken towards the lower index in both selection steps; the column
+L1 norm is the exact sum; pruned entries of the masked matrix are +0.0; a kept
+weight that happens to be zero still counts as kept (mask = 1 by position).
+
+All floating point is fp64.  |fp16| values are multiples of 2**-24 below 2**16,
+so a sum of V <= 8192 of them is exactly representable in fp64 whatever the
+summation order; the column norms below are therefore exact.
+
+Pins (tests/test_oracle_pins.py): pattern invariants, brute-force enumeration
+on tiny blocks, optimality of the kept mass, the M = 4 (plain 2:4) and V = 1
+(2-of-M per row) special cases, a hand-worked example, round trips, exact
+integer column sums, and for the matmul a triple-loop dot product, one-hot
+inputs and exactly representable small-integer products.  No function in this
+file is "parity unpinned"; the paper itself prints no numeric example of a
+pruned block (its figures are not part of the text), so the worked example is
+derived by hand from the Section 3 definition.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+N_KEPT = 2          # N is fixed to 2 (Section 4.1: N is identically 2)
+COLS_KEPT = 4       # every block keeps exactly four columns (Section 3, step 3)
+
+
+def padded_dims(out: int, inn: int, V: int, M: int):
+    """Padded shape, block counts (Section 3, weight padding).
+
+    Returns (out_pad, in_pad, R, B): rows padded to a multiple of V, columns to
+    a multiple of M, R = row blocks, B = column blocks.
+    """
+    if V < 1 or M < COLS_KEPT or out < 1 or inn < 1:
+        raise ValueError("need V >= 1, M >= 4, out >= 1, in >= 1")
+    R = -(-out // V)
+    B = -(-inn // M)
+    return R * V, B * M, R, B
+
+
+def _as_fp16_matrix(W) -> np.ndarray:
+    W = np.asarray(W)
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("expected a 2-D float16 array")
+    return W
+
+
+def pad_weight(W: np.ndarray, V: int, M: int) -> np.ndarray:
+    """Zero-extend W [out x in] to [out_pad x in_pad] (Section 3, padding)."""
+    W = _as_fp16_matrix(W)
+    out, inn = W.shape
+    out_pad, in_pad, _, _ = padded_dims(out, inn, V, M)
+    Wp = np.zeros((out_pad, in_pad), dtype=np.float16)
+    Wp[:out, :inn] = W
+    return Wp
+
+
+def importance_abs(Wp: np.ndarray) -> np.ndarray:
+    """Step 1 of Section 3 with the ABS criterion: score = |w|, in fp64."""
+    return np.abs(Wp.astype(np.float64))
+
+
+def column_l1(S: np.ndarray, V: int, M: int) -> np.ndarray:
+    """Step 2 of Section 3: L1 norm of every column of every V x M block.
+
+    S is the padded score matrix; returns L [R, B, M] with
+    L[r, b, c] = sum_v S[r*V + v, b*M + c].
+    """
+    out_pad, in_pad = S.shape
+    R, B = out_pad // V, in_pad // M
+    return S.reshape(R, V, B, M).sum(axis=1)
+
+
+def select_columns(L: np.ndarray) -> np.ndarray:
+    """Step 2 of Section 3: keep the four columns of largest L1 norm.
+
+    Sort key is (norm descending, index ascending); the survivors are stored in
+    ascending index order (Appendix A: relative positions are preserved).
+    Returns uint8 [R, B, 4].
+    """
+    order = np.argsort(-L, axis=-1, kind="stable")[..., :COLS_KEPT]
+    return np.sort(order, axis=-1).astype(np.uint8)
+
+
+def select_2_of_4(S: np.ndarray, colidx: np.ndarray, V: int, M: int) -> np.ndarray:
+    """Step 3 of Section 3: per row, keep the two largest scores among the
+    four surviving columns of the block; ties go to the lower position.
+
+    Returns pos uint8 [out_pad, B, 2] with pos[..., 0] < pos[..., 1], each the
+    position (0..3) of a kept value among the block's four surviving columns.
+    """
+    out_pad, in_pad = S.shape
+    R, B = out_pad // V, in_pad // M
+    blk = S.reshape(R, V, B, M)
+    idx = np.broadcast_to(colidx[:, None, :, :].astype(np.intp), (R, V, B, COLS_KEPT))
+    g = np.take_along_axis(blk, idx, axis=3)                     # [R, V, B, 4]
+    rank = np.argsort(-g, axis=-1, kind="stable")[..., :N_KEPT]
+    pos = np.sort(rank, axis=-1).astype(np.uint8)
+    return pos.reshape(out_pad, B, N_KEPT)
+
+
+def prune(W: np.ndarray, V: int, M: int, score: np.ndarray | None = None):
+    """The pruning operator S_{V:N:M} of Section 3 with N = 2.
+
+    W: fp16 [out x in].  score: optional fp64 [out x in] importance scores
+    (default: ABS).  Returns (colidx [R,B,4] u8, pos [out_pad,B,2] u8,
+    mask [out x in] u8).
+    """
+    W = _as_fp16_matrix(W)
+    out, inn = W.shape
+    out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
+    if score is None:
+        S = importance_abs(pad_weight(W, V, M))
+    else:
+        S = np.zeros((out_pad, in_pad), dtype=np.float64)
+        S[:out, :inn] = np.asarray(score, dtype=np.float64)
+    L = column_l1(S, V, M)
+    colidx = select_columns(L)
+    pos = select_2_of_4(S, colidx, V, M)
+    mask = mask_from_selection(colidx, pos, out, inn, V, M)
+    return colidx, pos, mask
+
+
+def kept_columns(colidx: np.ndarray, pos: np.ndarray, V: int, M: int) -> np.ndarray:
+    """Absolute padded column of every kept value: int64 [out_pad, B, 2]."""
+    out_pad, B, _ = pos.shape
+    R = out_pad // V
+    ci = np.repeat(colidx.astype(np.int64), V, axis=0)            # [out_pad, B, 4]
+    inblock = np.take_along_axis(ci, pos.astype(np.intp), axis=2)  # [out_pad, B, 2]
+    return inblock + (np.arange(B, dtype=np.int64) * M)[None, :, None]
+
+
+def mask_from_selection(colidx, pos, out: int, inn: int, V: int, M: int) -> np.ndarray:
+    """0-1 mask of Section 3 (W' = W (.) mask), reported on [out x in] only."""
+    out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
+    cols = kept_columns(colidx, pos, V, M)
+    mask = np.zeros((out_pad, in_pad), dtype=np.uint8)
+    rows = np.arange(out_pad, dtype=np.int64)[:, None, None]
+    mask[np.broadcast_to(rows, cols.shape), cols] = 1
+    return np.ascontiguousarray(mask[:out, :inn])
+
+
+def masked_dense(W: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """W' of Section 3: kept entries are bit copies, pruned entries are +0.0."""
+    W = _as_fp16_matrix(W)
+    return np.where(mask.astype(bool), W, np.float16(0.0)).astype(np.float16)
+
+
+def compress(W: np.ndarray, V: int, M: int, score: np.ndarray | None = None):
+    """Prune and convert to the compressed triple of Appendix A.
+
+    Returns (values, meta, colidx, mask):
+      values fp16 [out_pad x 2B]  -- A_n: the two kept values of block b of a
+                                     row sit at columns 2b, 2b+1 in ascending
+                                     position order;
+      meta   u8   [out_pad x ceil(B/2)] -- A_i2: nibble p0 | p1 << 2 per
+                                     (row, block); byte j holds block 2j in its
+                                     low nibble and block 2j+1 in its high one;
+      colidx u8   [R x B x 4]     -- A_i1: in-block indices of the four kept
+                                     columns, ascending;
+      mask   u8   [out x in].
+    """
+    W = _as_fp16_matrix(W)
+    out, inn = W.shape
+    out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
+    colidx, pos, mask = prune(W, V, M, score)
+    Wp = pad_weight(W, V, M)
+    cols = kept_columns(colidx, pos, V, M)
+    rows = np.broadcast_to(np.arange(out_pad, dtype=np.int64)[:, None, None], cols.shape)
+    values = np.ascontiguousarray(Wp[rows, cols].reshape(out_pad, 2 * B))
+    nib = (pos[..., 0] | (pos[..., 1] << 2)).astype(np.uint8)      # [out_pad, B]
+    if B % 2:
+        nib = np.concatenate([nib, np.zeros((out_pad, 1), np.uint8)], axis=1)
+    meta = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    return values, np.ascontiguousarray(meta), colidx, mask
+
+
+def unpack_meta(meta: np.ndarray, B: int) -> np.ndarray:
+    """Inverse of the nibble packing: pos u8 [out_pad, B, 2]."""
+    out_pad = meta.shape[0]
+    nib = np.empty((out_pad, 2 * meta.shape[1]), dtype=np.uint8)
+    nib[:, 0::2] = meta & 0x0F
+    nib[:, 1::2] = meta >> 4
+    nib = nib[:, :B]
+    return np.stack([nib & 3, (nib >> 2) & 3], axis=-1).astype(np.uint8)
+
+
+def decompress(values, meta, colidx, out: int, inn: int, V: int, M: int) -> np.ndarray:
+    """Scatter the compressed triple back to the dense fp16 W' [out x in]."""
+    out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
+    pos = unpack_meta(np.asarray(meta), B)
+    cols = kept_columns(np.asarray(colidx).reshape(R, B, COLS_KEPT), pos, V, M)
+    rows = np.broadcast_to(np.arange(out_pad, dtype=np.int64)[:, None, None], cols.shape)
+    Wd = np.zeros((out_pad, in_pad), dtype=np.float16)
+    Wd[rows, cols] = np.asarray(values).reshape(out_pad, B, N_KEPT)
+    return np.ascontiguousarray(Wd[:out, :inn])
+
+
+def matmul_ref(X: np.ndarray, Wm: np.ndarray) -> np.ndarray:
+    """Y = X . W'^T with fp64 products and fp64 accumulation.
+
+    X fp16 [T x in], Wm fp16 [out x in] (the masked dense matrix).  A product
+    of two fp16 numbers is exact in fp64.
+    """
+    return X.astype(np.float64) @ Wm.astype(np.float64).T
+
+
+def spmm_ref(X, values, meta, colidx, out: int, inn: int, V: int, M: int) -> np.ndarray:
+    """The sparse product written directly on the compressed triple:
+
+      Y[t, o] = sum_b sum_{j in {0,1}} values[o, 2b+j] * X[t, b*M + colidx[o//V, b, pos_j(o, b)]]
+
+    with X taken as 0 at padded columns.  fp64 throughout; returns [T x out].
+    """
+    X = np.asarray(X)
+    T = X.shape[0]
+    out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
+    pos = unpack_meta(np.asarray(meta), B)
+    cols = kept_columns(np.asarray(colidx).reshape(R, B, COLS_KEPT), pos, V, M)
+    Xp = np.zeros((T, in_pad), dtype=np.float64)
+    Xp[:, :inn] = X.astype(np.float64)
+    vals = np.asarray(values).astype(np.float64).reshape(out_pad, 2 * B)
+    cols = cols.reshape(out_pad, 2 * B)
+    Y = np.empty((T, out), dtype=np.float64)
+    for o in range(out):
+        Y[:, o] = Xp[:, cols[o]] @ vals[o]
+    return Y
+
+
+def max_normalised_error(Y, Y_ref) -> float:
+    """max |Y - Y_ref| / max |Y_ref| -- the acceptance measure for the product."""
+    Y_ref = np.asarray(Y_ref, dtype=np.float64)
+    denom = float(np.max(np.abs(Y_ref))) if Y_ref.size else 0.0
+    if denom == 0.0:
+        return float(np.max(np.abs(np.asarray(Y, dtype=np.float64)))) if Y_ref.size else 0.0
+    return float(np.max(np.abs(np.asarray(Y, dtype=np.float64) - Y_ref)) / denom)

@@ -1,0 +1,128 @@
+/*
+ * libvnm -- V:N:M sparse linear layers on AMD MI355X (gfx950), C ABI.
+ *
+ * The pattern (paper, abstract and Section 3 "Pruning of V:N:M sparsity"): a weight matrix
+ * W [out x in] is cut into V x M blocks (V rows, M consecutive input columns).  Each block keeps
+ * the 4 columns of largest column L1 norm of the importance score, and every row keeps the 2
+ * largest scores among those 4, so the density is 2/M and M = 4 is plain 2:4.  N is always 2
+ * (Section 4.1).  W is treated as zero-extended so that out is a multiple of V and in a multiple
+ * of M (Section 3 "Acceleration of V:N:M sparsity"); callers never pad anything themselves.
+ * Ties in both selections go to the lower index, which makes the mask unique.
+ *
+ * Compressed form (Appendix A), all row-major, all caller-allocated device memory:
+ *   values  fp16  [out_pad x 2*col_blocks]        A_n : the two kept values of block b of a row at
+ *                                                       columns 2b, 2b+1, ascending position
+ *   meta    u8    [out_pad x ceil(col_blocks/2)]  A_i2: one nibble p0 | p1 << 2 per (row, block),
+ *                                                       p0 < p1 the positions (0..3) of the kept
+ *                                                       values among the block's 4 kept columns;
+ *                                                       byte j = block 2j (low), 2j+1 (high nibble)
+ *   colidx  u8    [row_blocks x col_blocks x 4]   A_i1: in-block indices (0..M-1) of the 4 kept
+ *                                                       columns, ascending
+ *   packed  opaque, packed_bytes                  the same information re-ordered for the matrix
+ *                                                 cores; produced by vnm_prune_compress / vnm_pack,
+ *                                                 consumed by vnm_spmm; not a storage format
+ *
+ * Conventions: every function returns a vnm_status (0 = success) and never throws.  Pointers named
+ * in capitals or marked "dev" are device pointers; everything else is host.  The library never
+ * allocates or frees device memory and keeps no reference to any buffer after the enqueued work
+ * has run.  Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ * stream) and is asynchronous to the host.  Inputs are never written; outputs are fully
+ * overwritten, including the pad rows of values / meta (value +0.0, positions (0,1)).
+ * Argument errors are detected on the host before anything touches the device.
+ */
+#ifndef VNM_H
+#define VNM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VNM_FORMAT_VERSION 1
+
+typedef enum vnm_status {
+  VNM_OK = 0,
+  VNM_ERR_NULL = 1,        /* a required pointer is NULL */
+  VNM_ERR_SHAPE = 2,       /* out <= 0, in <= 0, T < 0, or a leading dimension below the row width */
+  VNM_ERR_UNSUPPORTED = 3, /* N != 2, M < 4 or M > 255, V not in {16, 32, 64, 128}, bad enum value */
+  VNM_ERR_ALIGN = 4,       /* a pointer violates the stated alignment */
+  VNM_ERR_WORKSPACE = 5,   /* workspace smaller than vnm_sizes.workspace_bytes */
+  VNM_ERR_HIP = 6          /* a HIP call or kernel launch failed; see vnm_last_hip_error() */
+} vnm_status;
+
+/* Sizes of everything the caller allocates for one layer (Section 3 padding; Appendix A triple). */
+typedef struct vnm_sizes {
+  int64_t out_pad;         /* ceil(out / V) * V */
+  int64_t in_pad;          /* ceil(in / M) * M */
+  int64_t row_blocks;      /* out_pad / V */
+  int64_t col_blocks;      /* in_pad / M */
+  int64_t kc;              /* compacted K = 4 * col_blocks */
+  int64_t values_elems;    /* out_pad * 2 * col_blocks  fp16 elements */
+  int64_t meta_bytes;      /* out_pad * ceil(col_blocks / 2) */
+  int64_t colidx_bytes;    /* row_blocks * col_blocks * 4 */
+  int64_t packed_bytes;    /* size of the opaque matrix-core copy (0 if this V, M has none) */
+  int64_t workspace_bytes; /* per-call scratch any entry point may ask for (currently 0) */
+} vnm_sizes;
+
+/* Which kernel vnm_spmm uses. */
+typedef enum vnm_spmm_path {
+  VNM_PATH_AUTO = 0,       /* sparse matrix-core kernel when `packed` is given and the shape allows, else generic */
+  VNM_PATH_GENERIC = 1,    /* scalar kernel on the canonical triple; any V, M, alignment */
+  VNM_PATH_SMFMAC = 2      /* 2:4 sparse MFMA kernel on `packed`; fails with UNSUPPORTED if not applicable */
+} vnm_spmm_path;
+
+/* Host only.  Fills *s for a layer of `out` x `in` at V:N:M. */
+int vnm_query_sizes(int64_t out, int64_t in, int V, int N, int M, vnm_sizes* s);
+
+/*
+ * Section 3, steps 1-3 with the ABS score, followed by the conversion of Appendix A.
+ *   W        dev, fp16 [out x in], row-major with leading dimension ldw >= in (elements); 2-byte aligned
+ *   values, meta, colidx   dev outputs, sizes from vnm_query_sizes
+ *   mask     dev u8 [out x in] (dense, leading dimension in) or NULL: the 0-1 mask of Section 3
+ *   packed   dev, packed_bytes, 256-byte aligned, or NULL
+ * Column norms are accumulated exactly (integer fixed point), so the result does not depend on any
+ * summation order.  Non-finite weights are not supported (result unspecified, no fault).
+ */
+int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_t ldw, int V, int N, int M,
+                       void* values, void* meta, void* colidx, void* mask, void* packed,
+                       void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Builds `packed` from an existing canonical triple (e.g. one loaded from storage). */
+int vnm_pack(const void* values, const void* meta, const void* colidx,
+             int64_t out, int64_t in, int V, int N, int M, void* packed, void* stream);
+
+/*
+ * Y = X . W'^T on the compressed weight (Section 3 "Acceleration"; Appendix A describes the kernel's
+ * job: fetch the kept weights and the matching input columns so that the layout is that of a 2:4
+ * product, then use the sparse matrix cores):
+ *   Y[t, o] = sum_b sum_{j<2} values[o, 2b+j] * X[t, b*M + colidx[o / V, b, pos_j(o, b)]],
+ * fp16 operands, fp32 accumulation; X counts as 0 at padded columns and is never read there.
+ *   X        dev fp16 [T x in], leading dimension ldx >= in
+ *   Y        dev [T x out], leading dimension ldy >= out; y_dtype 0 = fp16, 1 = fp32
+ *   packed   dev or NULL (NULL forces the generic kernel under VNM_PATH_AUTO)
+ *   path     a vnm_spmm_path
+ * The matrix-core kernel needs V in {32, 64, 128}, M <= 16, in % 8 == 0, ldx % 8 == 0 and X 16-byte
+ * aligned; otherwise AUTO falls back to the generic kernel.  T == 0 is a successful no-op.
+ */
+int vnm_spmm(const void* X, int64_t T, int64_t ldx,
+             const void* values, const void* meta, const void* colidx, const void* packed,
+             int64_t out, int64_t in, int V, int N, int M,
+             void* Y, int64_t ldy, int y_dtype, int path,
+             void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Inverse of the conversion of Appendix A: dense fp16 W' [out x in] (leading dimension ldw),
+ * kept values as bit copies, +0.0 everywhere else. */
+int vnm_decompress(const void* values, const void* meta, const void* colidx,
+                   int64_t out, int64_t in, int V, int N, int M,
+                   void* W_out, int64_t ldw, void* stream);
+
+const char* vnm_status_string(int status);
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char* vnm_last_hip_error(void);
+int vnm_format_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VNM_H */

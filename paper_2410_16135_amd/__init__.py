@@ -1,0 +1,11 @@
+"""V:N:M sparse linear layers for AMD MI355X: thin Python binding over the libvnm C ABI.
+
+The three calls of the hot path -- vnm_prune_compress, vnm_spmm, vnm_decompress -- run entirely in
+the HIP kernels of libvnm.so; this package only marshals arguments.  There is no CPU fallback: if
+the library is missing, importing the binding raises.
+"""
+
+from .binding import (  # noqa: F401
+    VnmError, VnmSizes, Compressed, lib_path, load_library, vnm_query_sizes, vnm_prune_compress,
+    vnm_pack, vnm_spmm, vnm_decompress, PATH_AUTO, PATH_GENERIC, PATH_SMFMAC,
+)

@@ -1,0 +1,157 @@
+"""ctypes binding of include/vnm.h.  PyTorch is used for device memory and streams only."""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+PATH_AUTO, PATH_GENERIC, PATH_SMFMAC = 0, 1, 2
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class VnmError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(what)
+
+
+class VnmSizes(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in (
+        "out_pad", "in_pad", "row_blocks", "col_blocks", "kc", "values_elems", "meta_bytes",
+        "colidx_bytes", "packed_bytes", "workspace_bytes")]
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG_DIR, "libvnm.so")
+
+
+def load_library():
+    """Load libvnm.so; build it first only if it has never been built.  Raises if neither works."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(path)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.vnm_query_sizes.argtypes = [i64, i64, ci, ci, ci, ctypes.POINTER(VnmSizes)]
+    lib.vnm_prune_compress.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.vnm_pack.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp]
+    lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
+    lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
+    for f in (lib.vnm_query_sizes, lib.vnm_prune_compress, lib.vnm_pack, lib.vnm_spmm, lib.vnm_decompress,
+              lib.vnm_format_version):
+        f.restype = ci
+    lib.vnm_status_string.argtypes = [ci]
+    lib.vnm_status_string.restype = ctypes.c_char_p
+    lib.vnm_last_hip_error.restype = ctypes.c_char_p
+    _LIB = lib
+    return lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        lib = load_library()
+        msg = lib.vnm_status_string(status).decode()
+        if status == 6:
+            msg += " (" + lib.vnm_last_hip_error().decode() + ")"
+        raise VnmError(status, f"{what}: {msg}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(t):
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def vnm_query_sizes(out: int, inn: int, V: int, M: int, N: int = 2) -> VnmSizes:
+    s = VnmSizes()
+    _check(load_library().vnm_query_sizes(out, inn, V, N, M, ctypes.byref(s)), "vnm_query_sizes")
+    return s
+
+
+@dataclass
+class Compressed:
+    """The compressed triple of one layer plus the opaque matrix-core copy (device tensors)."""
+    values: object
+    meta: object
+    colidx: object
+    packed: object
+    out: int
+    inn: int
+    V: int
+    M: int
+    mask: object = None
+
+
+def _alloc(sizes: VnmSizes, device, want_packed=True):
+    import torch
+    values = torch.empty(sizes.values_elems, dtype=torch.float16, device=device)
+    meta = torch.empty(sizes.meta_bytes, dtype=torch.uint8, device=device)
+    colidx = torch.empty(sizes.colidx_bytes, dtype=torch.uint8, device=device)
+    packed = None
+    if want_packed and sizes.packed_bytes > 0:
+        packed = torch.empty(sizes.packed_bytes, dtype=torch.uint8, device=device)
+    return values, meta, colidx, packed
+
+
+def vnm_prune_compress(W, V: int, M: int, N: int = 2, want_mask: bool = False, want_packed: bool = True,
+                       out=None) -> Compressed:
+    """W: fp16 CUDA tensor [out x in] (row stride may exceed `in`).  Allocates the outputs (or
+    reuses `out`, a Compressed of the same layer) and enqueues the kernel on the current stream."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    o, i = W.shape
+    sizes = vnm_query_sizes(o, i, V, M, N)
+    if out is None:
+        values, meta, colidx, packed = _alloc(sizes, W.device, want_packed)
+        mask = torch.empty((o, i), dtype=torch.uint8, device=W.device) if want_mask else None
+        out = Compressed(values, meta, colidx, packed, o, i, V, M, mask)
+    _check(load_library().vnm_prune_compress(
+        _ptr(W), o, i, W.stride(0), V, N, M, _ptr(out.values), _ptr(out.meta), _ptr(out.colidx),
+        _ptr(out.mask), _ptr(out.packed), None, 0, _stream(W)), "vnm_prune_compress")
+    return out
+
+
+def vnm_pack(c: Compressed, N: int = 2) -> Compressed:
+    import torch
+    sizes = vnm_query_sizes(c.out, c.inn, c.V, c.M, N)
+    if c.packed is None:
+        c.packed = torch.empty(sizes.packed_bytes, dtype=torch.uint8, device=c.values.device)
+    _check(load_library().vnm_pack(_ptr(c.values), _ptr(c.meta), _ptr(c.colidx), c.out, c.inn, c.V, N, c.M,
+                                   _ptr(c.packed), _stream(c.values)), "vnm_pack")
+    return c
+
+
+def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO, Y=None):
+    """Y [T x out] = X [T x in] . W'^T on the compressed weight; fp16 in, fp32 accumulate."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    T = X.shape[0]
+    assert X.shape[1] == c.inn
+    if Y is None:
+        Y = torch.empty((T, c.out), dtype=out_dtype or torch.float16, device=X.device)
+    y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    _check(load_library().vnm_spmm(
+        _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
+        _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
+        None, 0, _stream(X)), "vnm_spmm")
+    return Y
+
+
+def vnm_decompress(c: Compressed, N: int = 2, W_out=None):
+    import torch
+    if W_out is None:
+        W_out = torch.empty((c.out, c.inn), dtype=torch.float16, device=c.values.device)
+    _check(load_library().vnm_decompress(_ptr(c.values), _ptr(c.meta), _ptr(c.colidx), c.out, c.inn, c.V, N,
+                                         c.M, _ptr(W_out), W_out.stride(0), _stream(c.values)),
+           "vnm_decompress")
+    return W_out

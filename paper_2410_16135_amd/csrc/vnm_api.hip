@@ -1,0 +1,128 @@
+// C ABI of libvnm: argument validation on the host, then dispatch to the kernel launchers.
+#include <string.h>
+#include <stdio.h>
+#include "vnm_internal.h"
+
+namespace vnm {
+static thread_local char g_hip_error[256] = "";
+void set_hip_error(hipError_t e, const char* where) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", where, hipGetErrorString(e));
+}
+}  // namespace vnm
+
+using namespace vnm;
+
+static int check_pattern(int64_t out, int64_t in, int V, int N, int M) {
+  if (out <= 0 || in <= 0) return VNM_ERR_SHAPE;
+  if (N != 2) return VNM_ERR_UNSUPPORTED;                       // Section 4.1: N is always 2
+  if (M < 4 || M > 255) return VNM_ERR_UNSUPPORTED;             // colidx is a byte
+  if (!(V == 16 || V == 32 || V == 64 || V == 128)) return VNM_ERR_UNSUPPORTED;
+  return VNM_OK;
+}
+
+extern "C" int vnm_query_sizes(int64_t out, int64_t in, int V, int N, int M, vnm_sizes* s) {
+  if (!s) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  Dims d = make_dims(out, in, V, M);
+  s->out_pad = d.out_pad;
+  s->in_pad = d.in_pad;
+  s->row_blocks = d.R;
+  s->col_blocks = d.B;
+  s->kc = 4 * d.B;
+  s->values_elems = d.out_pad * 2 * d.B;
+  s->meta_bytes = d.out_pad * ((d.B + 1) / 2);
+  s->colidx_bytes = d.R * d.B * 4;
+  s->packed_bytes = packed_layout(d).total;
+  s->workspace_bytes = 0;
+  return VNM_OK;
+}
+
+extern "C" int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_t ldw, int V, int N,
+                                  int M, void* values, void* meta, void* colidx, void* mask,
+                                  void* packed, void* workspace, int64_t workspace_bytes,
+                                  void* stream) {
+  (void)workspace;
+  if (!W || !values || !meta || !colidx) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (ldw < in) return VNM_ERR_SHAPE;
+  if (workspace_bytes < 0) return VNM_ERR_WORKSPACE;
+  if (((uintptr_t)W & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
+  Dims d = make_dims(out, in, V, M);
+  if (packed) {
+    if (!has_packed(V, M)) return VNM_ERR_UNSUPPORTED;
+    if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  rc = launch_prune_compress(W, ldw, d, values, meta, colidx, mask, st);
+  if (rc) return rc;
+  if (packed) rc = launch_pack(values, meta, colidx, d, packed, st);
+  return rc;
+}
+
+extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx, int64_t out,
+                        int64_t in, int V, int N, int M, void* packed, void* stream) {
+  if (!values || !meta || !colidx || !packed) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (!has_packed(V, M)) return VNM_ERR_UNSUPPORTED;
+  if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
+  if ((uintptr_t)values & 3) return VNM_ERR_ALIGN;
+  return launch_pack(values, meta, colidx, make_dims(out, in, V, M), packed, (hipStream_t)stream);
+}
+
+extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                        const void* colidx, const void* packed, int64_t out, int64_t in, int V,
+                        int N, int M, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
+                        int64_t workspace_bytes, void* stream) {
+  (void)workspace;
+  if (!values || !meta || !colidx) return VNM_ERR_NULL;
+  if (T != 0 && (!X || !Y)) return VNM_ERR_NULL;                 // an empty batch may come with null X, Y
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (T < 0 || ldx < in || ldy < out) return VNM_ERR_SHAPE;
+  if (y_dtype != 0 && y_dtype != 1) return VNM_ERR_UNSUPPORTED;
+  if (path != VNM_PATH_AUTO && path != VNM_PATH_GENERIC && path != VNM_PATH_SMFMAC)
+    return VNM_ERR_UNSUPPORTED;
+  if (workspace_bytes < 0) return VNM_ERR_WORKSPACE;
+  if (((uintptr_t)X & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
+  if ((uintptr_t)Y & (y_dtype == 0 ? 1 : 3)) return VNM_ERR_ALIGN;
+  if (packed && ((uintptr_t)packed & 255)) return VNM_ERR_ALIGN;
+  if (T == 0) return VNM_OK;
+  Dims d = make_dims(out, in, V, M);
+  hipStream_t st = (hipStream_t)stream;
+  const bool fast_ok = packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d);
+  if (path == VNM_PATH_SMFMAC && !fast_ok) return VNM_ERR_UNSUPPORTED;
+  if (path != VNM_PATH_GENERIC && fast_ok)
+    return launch_spmm_smfmac(X, T, ldx, packed, d, Y, ldy, y_dtype, st);
+  return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, st);
+}
+
+extern "C" int vnm_decompress(const void* values, const void* meta, const void* colidx, int64_t out,
+                              int64_t in, int V, int N, int M, void* W_out, int64_t ldw,
+                              void* stream) {
+  if (!values || !meta || !colidx || !W_out) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (ldw < in) return VNM_ERR_SHAPE;
+  if (((uintptr_t)W_out & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
+  return launch_decompress(values, meta, colidx, make_dims(out, in, V, M), W_out, ldw,
+                           (hipStream_t)stream);
+}
+
+extern "C" const char* vnm_status_string(int status) {
+  switch (status) {
+    case VNM_OK: return "ok";
+    case VNM_ERR_NULL: return "null pointer";
+    case VNM_ERR_SHAPE: return "bad shape or leading dimension";
+    case VNM_ERR_UNSUPPORTED: return "unsupported V:N:M, dtype or path";
+    case VNM_ERR_ALIGN: return "misaligned pointer";
+    case VNM_ERR_WORKSPACE: return "workspace too small";
+    case VNM_ERR_HIP: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" const char* vnm_last_hip_error(void) { return vnm::g_hip_error; }
+extern "C" int vnm_format_version(void) { return VNM_FORMAT_VERSION; }

@@ -1,0 +1,177 @@
+// vnm_decompress, vnm_pack and the generic (scalar) vnm_spmm kernel.
+#include "vnm_internal.h"
+
+namespace vnm {
+
+// ---------------------------------------------------------------- decompress (Appendix A, inverse)
+// One thread per element of W' [out x in]: look up the block's kept columns and the row's two
+// positions, emit the kept value (bit copy) or +0.0.  Stores are fully coalesced.
+__global__ void __launch_bounds__(256)
+decompress_kernel(const unsigned short* __restrict__ values, const unsigned char* __restrict__ meta,
+                  const unsigned char* __restrict__ colidx, int64_t out, int64_t in, int V, int M,
+                  int64_t B, unsigned short* __restrict__ Wd, int64_t ldw, int64_t row0) {
+  const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = row0 + blockIdx.y;
+  if (col >= in) return;
+  const int64_t b = col / M;
+  const int ci = (int)(col - b * M);
+  const int64_t r = row / V;
+  const uchar4 k4 = *(const uchar4*)(colidx + (r * B + b) * 4);
+  const unsigned char k[4] = {k4.x, k4.y, k4.z, k4.w};
+  const unsigned byte = meta[row * ((B + 1) / 2) + (b >> 1)];
+  const unsigned nib = (b & 1) ? (byte >> 4) : (byte & 15u);
+  const unsigned pair = *(const unsigned*)(values + row * 2 * B + 2 * b);
+  unsigned short w = 0;
+  if (k[nib & 3] == ci) w = (unsigned short)(pair & 0xFFFFu);
+  else if (k[nib >> 2] == ci) w = (unsigned short)(pair >> 16);
+  Wd[row * ldw + col] = w;
+}
+
+int launch_decompress(const void* values, const void* meta, const void* colidx, const Dims& d,
+                      void* W_out, int64_t ldw, hipStream_t st) {
+  for (int64_t r0 = 0; r0 < d.out; r0 += 65535) {                // grid.y limit
+    const int64_t rows = d.out - r0 < 65535 ? d.out - r0 : 65535;
+    dim3 grid((unsigned)((d.in + 255) / 256), (unsigned)rows);
+    hipLaunchKernelGGL(decompress_kernel, grid, dim3(256), 0, st, (const unsigned short*)values,
+                       (const unsigned char*)meta, (const unsigned char*)colidx, d.out, d.in, d.V,
+                       d.M, d.B, (unsigned short*)W_out, ldw, r0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e, "decompress_kernel"); return VNM_ERR_HIP; }
+  }
+  return VNM_OK;
+}
+
+// ---------------------------------------------------------------- pack
+// Re-orders the canonical triple into the operand order of V_SMFMAC_F32_32X32X32_F16.
+// A K step covers 8 column blocks (32 compacted K).  In a 32-row tile, lane l = i + 32*h holds the
+// row i, and its 8 values e = 0..7 are the two kept values of blocks 4h + e/2 of the step; the 2-bit
+// position of value e sits at bits [2e+1 : 2e] of the lane's 16-bit index word.  Blocks beyond the
+// last real one get value 0 and positions (0, 1).
+__global__ void __launch_bounds__(256)
+pack_kernel(const unsigned short* __restrict__ values, const unsigned char* __restrict__ meta,
+            const unsigned char* __restrict__ colidx, int V, int M, int64_t R, int64_t B, int64_t S,
+            unsigned short* __restrict__ pa, unsigned short* __restrict__ pidx,
+            unsigned char* __restrict__ pcol) {
+  const int tiles = V / 32;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = R * S * tiles * 64;
+  if (gid < total) {
+    const int lane = (int)(gid & 63);
+    int64_t rest = gid >> 6;
+    const int at = (int)(rest % tiles); rest /= tiles;
+    const int64_t s = rest % S;
+    const int64_t r = rest / S;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t row = r * V + at * 32 + i;
+    unsigned short v[8];
+    unsigned idx = 0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int64_t b = s * 8 + 4 * h + g;
+      unsigned pair = 0, nib = 4;                                  // (0, 1)
+      if (b < B) {
+        pair = *(const unsigned*)(values + row * 2 * B + 2 * b);
+        const unsigned byte = meta[row * ((B + 1) / 2) + (b >> 1)];
+        nib = (b & 1) ? (byte >> 4) : (byte & 15u);
+      }
+      v[2 * g] = (unsigned short)(pair & 0xFFFFu);
+      v[2 * g + 1] = (unsigned short)(pair >> 16);
+      idx |= nib << (4 * g);
+    }
+    uint4 q;
+    q.x = v[0] | ((unsigned)v[1] << 16); q.y = v[2] | ((unsigned)v[3] << 16);
+    q.z = v[4] | ((unsigned)v[5] << 16); q.w = v[6] | ((unsigned)v[7] << 16);
+    *(uint4*)(pa + (((r * S + s) * tiles + at) * 64 + lane) * 8) = q;
+    pidx[((r * S + s) * 64 + lane) * tiles + at] = (unsigned short)idx;
+  }
+  // pcol: one thread per (r, s, h, kq): the four staged-row offsets of the lane class (h, kq).
+  // Load m of the B operand covers block blk(m, h) = 4*(m/2) + 2*h + (m%2) of the step.
+  const int64_t ncol_items = R * S * 8;
+  if (gid < ncol_items) {
+    const int kq = (int)(gid & 3), h = (int)((gid >> 2) & 1);
+    const int64_t rs = gid >> 3;
+    const int64_t s = rs % S, r = rs / S;
+    unsigned o = 0;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const int blk = 4 * (m >> 1) + 2 * h + (m & 1);
+      const int64_t b = s * 8 + blk;
+      const unsigned c = (b < B) ? colidx[(r * B + b) * 4 + kq] : (unsigned)kq;
+      o |= (unsigned)(blk * M + c) << (8 * m);
+    }
+    *(unsigned*)(pcol + gid * 4) = o;
+  }
+}
+
+int launch_pack(const void* values, const void* meta, const void* colidx, const Dims& d,
+                void* packed, hipStream_t st) {
+  const PackedLayout pl = packed_layout(d);
+  if (pl.total == 0) return VNM_ERR_UNSUPPORTED;
+  const int64_t total = d.R * d.S * (d.V / 32) * 64;
+  char* p = (char*)packed;
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     (const unsigned short*)values, (const unsigned char*)meta,
+                     (const unsigned char*)colidx, d.V, d.M, d.R, d.B, d.S,
+                     (unsigned short*)(p + pl.pa_off), (unsigned short*)(p + pl.pidx_off),
+                     (unsigned char*)(p + pl.pcol_off));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "pack_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
+// ---------------------------------------------------------------- generic spmm
+// One thread per output Y[t, o], written straight from the formula on the canonical triple.
+// Slow; it is the fallback for shapes the matrix-core kernel does not take and the cross-check
+// for that kernel.
+template <typename OutT>
+__global__ void __launch_bounds__(256)
+spmm_generic_kernel(const _Float16* __restrict__ X, int64_t T, int64_t ldx,
+                    const _Float16* __restrict__ values, const unsigned char* __restrict__ meta,
+                    const unsigned char* __restrict__ colidx, int64_t out, int64_t in, int V, int M,
+                    int64_t B, OutT* __restrict__ Y, int64_t ldy) {
+  const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t t = blockIdx.y;
+  if (o >= out) return;
+  const int64_t r = o / V;
+  const _Float16* xrow = X + t * ldx;
+  const _Float16* vrow = values + o * 2 * B;
+  const unsigned char* mrow = meta + o * ((B + 1) / 2);
+  const unsigned char* crow = colidx + r * B * 4;
+  float acc = 0.f;
+  for (int64_t b = 0; b < B; ++b) {
+    const unsigned byte = mrow[b >> 1];
+    const unsigned nib = (b & 1) ? (byte >> 4) : (byte & 15u);
+    const int64_t c0 = b * M + crow[b * 4 + (nib & 3)];
+    const int64_t c1 = b * M + crow[b * 4 + (nib >> 2)];
+    const float x0 = (c0 < in) ? (float)xrow[c0] : 0.f;
+    const float x1 = (c1 < in) ? (float)xrow[c1] : 0.f;
+    acc = fmaf((float)vrow[2 * b], x0, acc);
+    acc = fmaf((float)vrow[2 * b + 1], x1, acc);
+  }
+  Y[t * ldy + o] = (OutT)acc;
+}
+
+int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                        const void* colidx, const Dims& d, void* Y, int64_t ldy, int y_dtype,
+                        hipStream_t st) {
+  const unsigned gx = (unsigned)((d.out + 255) / 256);
+  for (int64_t t0 = 0; t0 < T; t0 += 65535) {                    // grid.y limit
+    const int64_t nt = T - t0 < 65535 ? T - t0 : 65535;
+    const _Float16* Xs = (const _Float16*)X + t0 * ldx;
+    if (y_dtype == 0)
+      hipLaunchKernelGGL(spmm_generic_kernel<_Float16>, dim3(gx, (unsigned)nt), dim3(256), 0, st, Xs,
+                         nt, ldx, (const _Float16*)values, (const unsigned char*)meta,
+                         (const unsigned char*)colidx, d.out, d.in, d.V, d.M, d.B,
+                         (_Float16*)Y + t0 * ldy, ldy);
+    else
+      hipLaunchKernelGGL(spmm_generic_kernel<float>, dim3(gx, (unsigned)nt), dim3(256), 0, st, Xs,
+                         nt, ldx, (const _Float16*)values, (const unsigned char*)meta,
+                         (const unsigned char*)colidx, d.out, d.in, d.V, d.M, d.B,
+                         (float*)Y + t0 * ldy, ldy);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e, "spmm_generic_kernel"); return VNM_ERR_HIP; }
+  }
+  return VNM_OK;
+}
+
+}  // namespace vnm

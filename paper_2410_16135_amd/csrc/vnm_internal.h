@@ -1,0 +1,67 @@
+// Internal declarations shared by the HIP sources of libvnm (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "vnm.h"
+
+namespace vnm {
+
+// Padded shape of one layer (Section 3, weight padding) plus the tiling of the packed copy.
+struct Dims {
+  int64_t out, in, out_pad, in_pad;
+  int64_t R;       // row blocks
+  int64_t B;       // column blocks
+  int64_t S;       // K steps of the matrix-core kernel: groups of 8 column blocks (32 compacted K)
+  int V, M;
+};
+
+// Byte offsets of the three sections of the packed copy.
+//   pa   fp16 [R][S][V/32][64 lanes][8]   A operand of smfmac 32x32x32 in lane order
+//   pidx u16  [R][S][64 lanes][V/32]      2-bit positions, 16 bits per (lane, 32-row tile)
+//   pcol u8   [R][S][2][4][4]             staged-row offsets blk*M + c in B-operand lane order
+struct PackedLayout {
+  int64_t pa_off, pidx_off, pcol_off, total;
+};
+
+inline Dims make_dims(int64_t out, int64_t in, int V, int M) {
+  Dims d;
+  d.out = out; d.in = in; d.V = V; d.M = M;
+  d.R = (out + V - 1) / V;
+  d.B = (in + M - 1) / M;
+  d.out_pad = d.R * V;
+  d.in_pad = d.B * M;
+  d.S = (d.B + 7) / 8;
+  return d;
+}
+
+inline bool has_packed(int V, int M) { return (V == 32 || V == 64 || V == 128) && M <= 16; }
+
+inline PackedLayout packed_layout(const Dims& d) {
+  PackedLayout p{0, 0, 0, 0};
+  if (!has_packed(d.V, d.M)) return p;
+  auto up = [](int64_t x) { return (x + 255) / 256 * 256; };
+  const int64_t tiles = d.V / 32;
+  p.pa_off = 0;
+  p.pidx_off = up(d.R * d.S * tiles * 64 * 8 * 2);
+  p.pcol_off = p.pidx_off + up(d.R * d.S * 64 * tiles * 2);
+  p.total = p.pcol_off + up(d.R * d.S * 32);
+  return p;
+}
+
+void set_hip_error(hipError_t e, const char* where);
+
+// launchers (each returns a vnm_status)
+int launch_prune_compress(const void* W, int64_t ldw, const Dims& d, void* values, void* meta,
+                          void* colidx, void* mask, hipStream_t st);
+int launch_pack(const void* values, const void* meta, const void* colidx, const Dims& d,
+                void* packed, hipStream_t st);
+int launch_decompress(const void* values, const void* meta, const void* colidx, const Dims& d,
+                      void* W_out, int64_t ldw, hipStream_t st);
+int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                        const void* colidx, const Dims& d, void* Y, int64_t ldy, int y_dtype,
+                        hipStream_t st);
+bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d);
+int launch_spmm_smfmac(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+                       void* Y, int64_t ldy, int y_dtype, hipStream_t st);
+
+}  // namespace vnm

@@ -8,8 +8,9 @@ not used): W ~ N(0, 0.02^2), X ~ N(0, 1), drawn in fp32 and rounded to fp16
 (round to nearest even).  For the Llama-shaped layers 1 % of the input columns
 of W are multiplied by 10 to imitate outlier channels.
 
-Draw order for one layer: W first, then X, then the outlier column choice, all
-from numpy.random.default_rng(seed).
+Draw order for one layer: W first, then the outlier column choice, then X, all
+from numpy.random.default_rng(seed); W therefore does not depend on the token
+count, and a shorter X is a prefix of a longer one.
 """
 
 from __future__ import annotations
@@ -36,18 +37,17 @@ def make_weight_and_input(out: int, inn: int, tokens: int, seed: int,
     """Return (W fp16 [out x in], X fp16 [tokens x in])."""
     rng = np.random.default_rng(seed)
     W = rng.standard_normal((out, inn), dtype=np.float32) * np.float32(w_std)
-    X = rng.standard_normal((tokens, inn), dtype=np.float32)
     if outliers:
         n_out = int(round(0.01 * inn))
         cols = rng.choice(inn, size=n_out, replace=False)
         W[:, cols] *= np.float32(10.0)
+    X = rng.standard_normal((tokens, inn), dtype=np.float32)
     return W.astype(np.float16), X.astype(np.float16)
 
 
 def layer_tensors(layer: Layer, tokens: int | None = None):
-    """W and X of a Layer; `tokens` overrides the token count.  W is drawn first
-    and X row-major next, so W and the leading rows of X do not depend on the
-    count (the outlier column choice, drawn last, does)."""
+    """W and X of a Layer; `tokens` overrides the token count (W is unchanged
+    and the shorter X is a prefix of the longer one)."""
     T = layer.tokens if tokens is None else tokens
     return make_weight_and_input(layer.out, layer.inn, T, layer.seed, layer.outliers)
 

@@ -1,0 +1,90 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before touching any device (no GPU needed)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2410_16135_amd as vnm
+from oracle import vnm_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return vnm.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    with open(os.path.join(ROOT, "include", "vnm.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(vnm_[a-z_]+)\s*\(", text))
+    assert {"vnm_query_sizes", "vnm_prune_compress", "vnm_pack", "vnm_spmm", "vnm_decompress",
+            "vnm_status_string", "vnm_last_hip_error", "vnm_format_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.vnm_format_version() == 1
+
+
+@pytest.mark.parametrize("out,inn,V,M", [(128, 128, 64, 8), (4096, 4096, 64, 5), (11008, 4096, 128, 7),
+                                         (384, 1536, 64, 5), (100, 37, 16, 6), (4096, 11008, 32, 16)])
+def test_query_sizes_match_padding_rule(out, inn, V, M):
+    s = vnm.vnm_query_sizes(out, inn, V, M)
+    out_pad, in_pad, R, B = orc.padded_dims(out, inn, V, M)
+    assert (s.out_pad, s.in_pad, s.row_blocks, s.col_blocks) == (out_pad, in_pad, R, B)
+    assert s.kc == 4 * B and s.values_elems == out_pad * 2 * B
+    assert s.meta_bytes == out_pad * ((B + 1) // 2) and s.colidx_bytes == R * B * 4
+    assert (s.packed_bytes > 0) == (V in (32, 64, 128) and M <= 16)
+    assert s.packed_bytes % 256 == 0
+
+
+def test_argument_errors(lib):
+    s = vnm.VnmSizes()
+    q = lambda *a: lib.vnm_query_sizes(*a, ctypes.byref(s))
+    assert q(128, 128, 64, 2, 8) == 0
+    assert q(0, 128, 64, 2, 8) == 2 and q(128, -1, 64, 2, 8) == 2            # shape
+    assert q(128, 128, 64, 1, 8) == 3 and q(128, 128, 64, 4, 8) == 3         # N must be 2
+    assert q(128, 128, 64, 2, 3) == 3 and q(128, 128, 64, 2, 256) == 3       # M range
+    assert q(128, 128, 48, 2, 8) == 3 and q(128, 128, 8, 2, 8) == 3          # V set
+    assert lib.vnm_query_sizes(128, 128, 64, 2, 8, None) == 1                # null
+    # the device entry points validate on the host first: fake non-null pointers are never dereferenced
+    P = ctypes.c_void_p
+    good = P(0x1000)
+    assert lib.vnm_prune_compress(None, 128, 128, 128, 64, 2, 8, good, good, good, None, None, None, 0, None) == 1
+    assert lib.vnm_prune_compress(good, 128, 128, 64, 64, 2, 8, good, good, good, None, None, None, 0, None) == 2
+    assert lib.vnm_prune_compress(good, 128, 128, 128, 64, 3, 8, good, good, good, None, None, None, 0, None) == 3
+    assert lib.vnm_prune_compress(P(0x1001), 128, 128, 128, 64, 2, 8, good, good, good, None, None, None, 0, None) == 4
+    assert lib.vnm_prune_compress(good, 128, 128, 128, 64, 2, 8, good, good, good, None, P(0x1010), None, 0, None) == 4
+    assert lib.vnm_prune_compress(good, 128, 128, 128, 16, 2, 8, good, good, good, None, good, None, 0, None) == 3
+    assert lib.vnm_prune_compress(good, 128, 128, 128, 64, 2, 8, good, good, good, None, None, None, -1, None) == 5
+    assert lib.vnm_spmm(None, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 1
+    assert lib.vnm_spmm(good, -1, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 2
+    assert lib.vnm_spmm(good, 4, 127, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 2
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 100, 0, 0, None, 0, None) == 2
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 2, 0, None, 0, None) == 3
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 9, None, 0, None) == 3
+    # forcing the matrix-core path without a packed copy is refused, not silently rerouted
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 2, None, 0, None) == 3
+    # T == 0 is a successful no-op that touches nothing
+    assert lib.vnm_spmm(good, 0, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 0
+    assert lib.vnm_decompress(good, good, good, 128, 128, 64, 2, 8, None, 128, None) == 1
+    assert lib.vnm_decompress(good, good, good, 128, 128, 64, 2, 8, good, 5, None) == 2
+    assert lib.vnm_pack(good, good, good, 128, 128, 16, 2, 8, good, None) == 3
+    assert lib.vnm_pack(good, good, good, 128, 128, 64, 2, 8, P(0x1008), None) == 4
+    assert lib.vnm_status_string(0) == b"ok" and b"null" in lib.vnm_status_string(1)
+
+
+def test_package_has_no_cpu_fallback():
+    """The product package must not import the oracle (nor the oracle the package)."""
+    pkg = os.path.join(ROOT, "paper_2410_16135_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                with open(os.path.join(dirpath, fn)) as f:
+                    assert "oracle" not in f.read(), fn
+    with open(os.path.join(ROOT, "oracle", "vnm_oracle.py")) as f:
+        assert "paper_2410_16135_amd" not in f.read()

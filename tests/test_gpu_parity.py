@@ -1,0 +1,221 @@
+"""GPU parity: every call of the hot path through the C ABI against the CPU oracle, element by
+element.  Masks, column indices, positions and kept values must be bit-exact; the product must stay
+within 1e-2 of the fp64 oracle, normalised by max |Y_ref| (fp16 operands, fp32 accumulation)."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2410_16135_amd as vnm
+import synth_inputs as syn
+from oracle import vnm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _check_compressed(c, W, V, M, with_mask=True):
+    values, meta, colidx, mask = orc.compress(W, V, M)
+    assert np.array_equal(c.colidx.cpu().numpy(), colidx.reshape(-1)), "colidx"
+    assert np.array_equal(c.meta.cpu().numpy(), meta.reshape(-1)), "meta"
+    assert np.array_equal(c.values.cpu().numpy().view(np.uint16), values.reshape(-1).view(np.uint16)), "values"
+    if with_mask:
+        assert np.array_equal(c.mask.cpu().numpy(), mask), "mask"
+    return values, meta, colidx, mask
+
+
+def _rand_w(rng, out, inn, kind):
+    if kind == "normal":
+        return (rng.standard_normal((out, inn)) * 0.02).astype(np.float16)
+    if kind == "ints":
+        return rng.integers(-2, 3, size=(out, inn)).astype(np.float16)
+    if kind == "wide":           # subnormals up to large values, signed zeros
+        W = (rng.standard_normal((out, inn)) * 10.0 ** rng.integers(-7, 4, size=(out, inn))).astype(np.float16)
+        W[rng.random(W.shape) < 0.05] = np.float16(-0.0)
+        return W
+    raise ValueError(kind)
+
+
+PRUNE_CASES = [
+    # out, in, V, M
+    (128, 128, 64, 8), (64, 40, 16, 5), (200, 333, 32, 5), (130, 77, 64, 7), (256, 96, 128, 6),
+    (96, 64, 32, 4), (64, 512, 64, 16), (48, 200, 16, 33), (100, 1030, 32, 5), (64, 510, 64, 255),
+]
+
+
+@pytest.mark.parametrize("out,inn,V,M", PRUNE_CASES)
+@pytest.mark.parametrize("kind", ["normal", "ints", "wide"])
+def test_prune_compress_bit_exact(out, inn, V, M, kind):
+    rng = np.random.default_rng(out * 7 + inn * 3 + V + M)
+    W = _rand_w(rng, out, inn, kind)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    torch.cuda.synchronize()
+    values, meta, colidx, mask = _check_compressed(c, W, V, M)
+    # decompress(compress(W)) is the masked dense matrix, bit for bit
+    Wd = vnm.vnm_decompress(c).cpu().numpy()
+    assert np.array_equal(Wd.view(np.uint16), orc.masked_dense(W, mask).view(np.uint16))
+
+
+def test_prune_compress_strided_input_and_degenerate_blocks():
+    rng = np.random.default_rng(5)
+    big = _rand_w(rng, 96, 160, "normal")
+    big[:, 10:30] = 0                       # all-zero blocks
+    big[32:64, :] = np.float16(0.25)        # all-equal rows
+    Wt = _dev(big)[:, :100]                 # leading dimension 160, width 100
+    W = big[:, :100].copy()
+    c = vnm.vnm_prune_compress(Wt, 32, 5, want_mask=True)
+    torch.cuda.synchronize()
+    _check_compressed(c, W, 32, 5)
+
+
+SPMM_CASES = [
+    # out, in, T, V, M
+    (128, 128, 16, 64, 8), (128, 128, 1, 64, 8), (192, 160, 130, 64, 5), (96, 200, 300, 32, 5),
+    (256, 264, 77, 128, 6), (130, 96, 200, 64, 7), (64, 640, 257, 64, 16), (160, 128, 64, 32, 4),
+    (100, 72, 50, 32, 9), (384, 384, 520, 64, 5),
+]
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", SPMM_CASES)
+@pytest.mark.parametrize("path", [vnm.PATH_GENERIC, vnm.PATH_SMFMAC])
+@pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
+def test_spmm_matches_oracle(out, inn, T, V, M, path, ydt):
+    rng = np.random.default_rng(out + inn + T + V + M)
+    W = _rand_w(rng, out, inn, "normal")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=ydt, path=path)
+    torch.cuda.synchronize()
+    values, meta, colidx, mask = _check_compressed(c, W, V, M)
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, mask))
+    assert Y.shape == (T, out)
+    assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
+
+
+@pytest.mark.parametrize("path", [vnm.PATH_GENERIC, vnm.PATH_SMFMAC])
+@pytest.mark.parametrize("out,inn,T,V,M", [(128, 160, 70, 64, 5), (256, 128, 33, 128, 8), (96, 120, 129, 32, 6)])
+def test_spmm_small_integers_exact(out, inn, T, V, M, path):
+    """Integer-valued operands: every product and partial sum is exact in fp32, so the result must
+    equal the oracle exactly -- a zero-tolerance check of the indexing."""
+    W, X = syn.small_integer_case(out, inn, T, seed=out + T)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float32, path=path)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, V, M)
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, mask))
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), Y_ref)
+
+
+def test_spmm_one_hot_reads_back_masked_weights():
+    rng = np.random.default_rng(3)
+    out, inn, V, M = 128, 120, 64, 5
+    W = _rand_w(rng, out, inn, "normal")
+    X = np.eye(inn, dtype=np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float16, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, V, M)
+    Wm = orc.masked_dense(W, mask)
+    assert np.array_equal(Y.cpu().numpy().T.view(np.uint16) & 0x7FFF, Wm.view(np.uint16) & 0x7FFF)
+
+
+def test_spmm_edge_cases():
+    rng = np.random.default_rng(9)
+    out, inn, V, M = 128, 128, 64, 8
+    W = _rand_w(rng, out, inn, "normal")
+    c = vnm.vnm_prune_compress(_dev(W), V, M)
+    # T == 0: no-op
+    Y = vnm.vnm_spmm(torch.empty((0, inn), dtype=torch.float16, device=DEV), c)
+    assert Y.shape == (0, out)
+    # in not a multiple of 8: AUTO must fall back to the generic kernel; forcing smfmac is refused
+    W2 = _rand_w(rng, 64, 100, "normal"); X2 = rng.standard_normal((40, 100)).astype(np.float16)
+    c2 = vnm.vnm_prune_compress(_dev(W2), 32, 5, want_mask=True)
+    Y2 = vnm.vnm_spmm(_dev(X2), c2, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X2, orc.masked_dense(W2, c2.mask.cpu().numpy()))
+    assert orc.max_normalised_error(Y2.cpu().numpy(), Y_ref) <= TOL
+    with pytest.raises(vnm.VnmError):
+        vnm.vnm_spmm(_dev(X2), c2, path=vnm.PATH_SMFMAC)
+    # strided X and Y (leading dimensions above the widths)
+    Xbig = _dev(rng.standard_normal((50, 256)).astype(np.float16))
+    Xv = Xbig[:, :inn]
+    Ybig = torch.zeros((50, 200), dtype=torch.float16, device=DEV)
+    vnm.vnm_spmm(Xv, c, Y=Ybig[:, :out], path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    values, meta, colidx, mask = orc.compress(W, V, M)
+    Y_ref = orc.matmul_ref(Xv.cpu().numpy(), orc.masked_dense(W, mask))
+    assert orc.max_normalised_error(Ybig[:, :out].float().cpu().numpy(), Y_ref) <= TOL
+    assert torch.all(Ybig[:, out:] == 0)                         # nothing written outside Y
+    # pack from a stored canonical triple gives the same product
+    c3 = vnm.Compressed(c.values, c.meta, c.colidx, None, out, inn, V, M)
+    vnm.vnm_pack(c3)
+    Y3 = vnm.vnm_spmm(Xv, c3, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    assert torch.equal(Y3, Ybig[:, :out])
+
+
+def test_spmm_pad_columns_are_never_read():
+    """in = 72 at M = 5 pads to 75: the pad columns must count as zero even when the memory right
+    after each X row holds NaN."""
+    rng = np.random.default_rng(4)
+    out, inn, T, V, M = 64, 72, 40, 32, 5
+    W = _rand_w(rng, out, inn, "normal")
+    Xfull = np.full((T, 80), np.nan, dtype=np.float16)
+    Xfull[:, :inn] = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Xd = _dev(Xfull)[:, :inn]
+    for path in (vnm.PATH_GENERIC, vnm.PATH_SMFMAC):
+        Y = vnm.vnm_spmm(Xd, c, out_dtype=torch.float32, path=path)
+        torch.cuda.synchronize()
+        Y_ref = orc.matmul_ref(Xfull[:, :inn], orc.masked_dense(W, c.mask.cpu().numpy()))
+        assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
+
+
+def test_config0_single_gemm():
+    (layer,) = syn.config_single_gemm()
+    W, X = syn.layer_tensors(layer)
+    c = vnm.vnm_prune_compress(_dev(W), layer.V, layer.M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, layer.V, layer.M)
+    assert orc.max_normalised_error(Y.cpu().numpy(), orc.matmul_ref(X, orc.masked_dense(W, mask))) <= TOL
+
+
+@pytest.mark.parametrize("cfg", ["deit_small", "deit_base"])
+def test_deit_shaped_layers_full(cfg):
+    layers = syn.config_deit_small() if cfg == "deit_small" else syn.config_deit_base()
+    for layer in layers:
+        W, X = syn.layer_tensors(layer)
+        c = vnm.vnm_prune_compress(_dev(W), layer.V, layer.M, want_mask=True)
+        Y = vnm.vnm_spmm(_dev(X), c, path=vnm.PATH_SMFMAC)
+        torch.cuda.synchronize()
+        _, _, _, mask = _check_compressed(c, W, layer.V, layer.M)
+        Y_ref = orc.matmul_ref(X, orc.masked_dense(W, mask))
+        err = orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref)
+        assert err <= TOL, (layer.name, err)
+
+
+@pytest.mark.parametrize("which", [0, 4, 6])
+def test_llama_shaped_layers_sampled_tokens(which):
+    """Full-size Llama-2-7B-shaped layers in the benchmark's launch configuration (T = 4096);
+    the oracle product is computed for 256 sampled tokens over all output channels."""
+    layer = syn.config_llama2_7b()[which]
+    W, X = syn.layer_tensors(layer)
+    c = vnm.vnm_prune_compress(_dev(W), layer.V, layer.M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, path=vnm.PATH_SMFMAC)
+    Wd = vnm.vnm_decompress(c)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, layer.V, layer.M)
+    Wm = orc.masked_dense(W, mask)
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint16), Wm.view(np.uint16))
+    rng = np.random.default_rng(99)
+    tok = np.sort(rng.choice(layer.tokens, size=256, replace=False))
+    tok[0], tok[-1] = 0, layer.tokens - 1
+    Y_ref = orc.matmul_ref(X[tok], Wm)
+    err = orc.max_normalised_error(Y[torch.from_numpy(tok).to(DEV)].float().cpu().numpy(), Y_ref)
+    assert err <= TOL, err

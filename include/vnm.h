@@ -62,7 +62,8 @@ typedef struct vnm_sizes {
   int64_t meta_bytes;      /* out_pad * ceil(col_blocks / 2) */
   int64_t colidx_bytes;    /* row_blocks * col_blocks * 4 */
   int64_t packed_bytes;    /* size of the opaque matrix-core copy (0 if this V, M has none) */
-  int64_t workspace_bytes; /* per-call scratch any entry point may ask for (currently 0) */
+  int64_t workspace_bytes; /* scratch of vnm_prune_compress (currently 0); vnm_spmm's depends on the
+                              token count, see vnm_spmm_workspace_bytes */
 } vnm_sizes;
 
 /* Which kernel vnm_spmm uses. */
@@ -102,14 +103,24 @@ int vnm_pack(const void* values, const void* meta, const void* colidx,
  *   Y        dev [T x out], leading dimension ldy >= out; y_dtype 0 = fp16, 1 = fp32
  *   packed   dev or NULL (NULL forces the generic kernel under VNM_PATH_AUTO)
  *   path     a vnm_spmm_path
+ *   workspace  dev, 256-byte aligned, at least vnm_spmm_workspace_bytes(T, ...) bytes: the
+ *            matrix-core kernel first re-lays X there (token tiles x K steps, column-major inside,
+ *            the order it streams through LDS); contents are scratch, nothing persists
  * The matrix-core kernel needs V in {32, 64, 128}, M <= 16, in % 8 == 0, ldx % 8 == 0 and X 16-byte
- * aligned; otherwise AUTO falls back to the generic kernel.  T == 0 is a successful no-op.
+ * aligned; otherwise (or when `packed` is NULL) AUTO uses the generic kernel, which needs no
+ * workspace.  When the matrix-core kernel applies but the workspace is missing or too small the
+ * call fails with VNM_ERR_WORKSPACE instead of silently taking the slow kernel.
+ * T == 0 is a successful no-op (X and Y may then be NULL).
  */
 int vnm_spmm(const void* X, int64_t T, int64_t ldx,
              const void* values, const void* meta, const void* colidx, const void* packed,
              int64_t out, int64_t in, int V, int N, int M,
              void* Y, int64_t ldy, int y_dtype, int path,
              void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Host only.  Bytes of workspace vnm_spmm needs for T tokens of this layer (0 if the matrix-core
+ * kernel does not exist for this V, M). */
+int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M, int64_t* bytes);
 
 /* Inverse of the conversion of Appendix A: dense fp16 W' [out x in] (leading dimension ldw),
  * kept values as bit copies, +0.0 everywhere else. */

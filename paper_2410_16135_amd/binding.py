@@ -44,6 +44,8 @@ def load_library():
     lib.vnm_pack.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp]
     lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
+    lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
+    lib.vnm_spmm_workspace_bytes.restype = ci
     for f in (lib.vnm_query_sizes, lib.vnm_prune_compress, lib.vnm_pack, lib.vnm_spmm, lib.vnm_decompress,
               lib.vnm_format_version):
         f.restype = ci
@@ -131,8 +133,30 @@ def vnm_pack(c: Compressed, N: int = 2) -> Compressed:
     return c
 
 
-def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO, Y=None):
-    """Y [T x out] = X [T x in] . W'^T on the compressed weight; fp16 in, fp32 accumulate."""
+def vnm_spmm_workspace_bytes(T: int, c: Compressed, N: int = 2) -> int:
+    b = ctypes.c_int64(0)
+    _check(load_library().vnm_spmm_workspace_bytes(T, c.out, c.inn, c.V, N, c.M, ctypes.byref(b)),
+           "vnm_spmm_workspace_bytes")
+    return b.value
+
+
+_WORKSPACES = {}
+
+
+def _workspace(device, nbytes: int):
+    """One grow-only scratch tensor per device, shared by all vnm_spmm calls of this process."""
+    import torch
+    ws = _WORKSPACES.get(device)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device)
+        _WORKSPACES[device] = ws
+    return ws
+
+
+def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO, Y=None, workspace=None):
+    """Y [T x out] = X [T x in] . W'^T on the compressed weight; fp16 in, fp32 accumulate.
+    `workspace`: optional uint8 CUDA tensor of at least vnm_spmm_workspace_bytes(T, c) bytes;
+    by default a process-wide grow-only scratch tensor is used."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
     T = X.shape[0]
@@ -140,10 +164,15 @@ def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO
     if Y is None:
         Y = torch.empty((T, c.out), dtype=out_dtype or torch.float16, device=X.device)
     y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    ws, ws_bytes = None, 0
+    if path != PATH_GENERIC and c.packed is not None and T > 0:
+        ws_bytes = vnm_spmm_workspace_bytes(T, c, N)
+        ws = workspace if workspace is not None else _workspace(X.device, ws_bytes)
+        ws_bytes = ws.numel()
     _check(load_library().vnm_spmm(
         _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
         _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
-        None, 0, _stream(X)), "vnm_spmm")
+        _ptr(ws), ws_bytes, _stream(X)), "vnm_spmm")
     return Y
 
 

@@ -76,7 +76,6 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
                         const void* colidx, const void* packed, int64_t out, int64_t in, int V,
                         int N, int M, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
                         int64_t workspace_bytes, void* stream) {
-  (void)workspace;
   if (!values || !meta || !colidx) return VNM_ERR_NULL;
   if (T != 0 && (!X || !Y)) return VNM_ERR_NULL;                 // an empty batch may come with null X, Y
   int rc = check_pattern(out, in, V, N, M);
@@ -94,9 +93,25 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
   hipStream_t st = (hipStream_t)stream;
   const bool fast_ok = packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d);
   if (path == VNM_PATH_SMFMAC && !fast_ok) return VNM_ERR_UNSUPPORTED;
-  if (path != VNM_PATH_GENERIC && fast_ok)
-    return launch_spmm_smfmac(X, T, ldx, packed, d, Y, ldy, y_dtype, st);
+  if (path != VNM_PATH_GENERIC && fast_ok) {
+    // the matrix-core kernel streams a re-laid copy of X that lives in the caller's workspace
+    if (!workspace || workspace_bytes < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 255) return VNM_ERR_ALIGN;
+    rc = launch_stage_x(X, T, ldx, d, workspace, st);
+    if (rc) return rc;
+    return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, st);
+  }
   return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, st);
+}
+
+extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
+                                       int64_t* bytes) {
+  if (!bytes) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (T < 0) return VNM_ERR_SHAPE;
+  *bytes = has_packed(V, M) ? staged_bytes(T, make_dims(out, in, V, M)) : 0;
+  return VNM_OK;
 }
 
 extern "C" int vnm_decompress(const void* values, const void* meta, const void* colidx, int64_t out,

@@ -48,6 +48,12 @@ inline PackedLayout packed_layout(const Dims& d) {
   return p;
 }
 
+// Staged activations (see vnm_stage.hip): token tiles of kTokTile, image rows kImagePitch bytes apart.
+constexpr int kTokTile = 128;
+constexpr int kImagePitch = kTokTile * 2 + 64;
+inline int64_t image_bytes(int M) { return ((int64_t)8 * M * kImagePitch + 1023) / 1024 * 1024; }
+int64_t staged_bytes(int64_t T, const Dims& d);
+
 void set_hip_error(hipError_t e, const char* where);
 
 // launchers (each returns a vnm_status)
@@ -60,8 +66,9 @@ int launch_decompress(const void* values, const void* meta, const void* colidx, 
 int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                         const void* colidx, const Dims& d, void* Y, int64_t ldy, int y_dtype,
                         hipStream_t st);
+int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st);
 bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d);
-int launch_spmm_smfmac(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, hipStream_t st);
 
 }  // namespace vnm

@@ -5,20 +5,22 @@
 // from plain 2:4 (Appendix A) is that the B rows a row block needs are the 4 kept input columns of
 // each of its column blocks, and they differ from row block to row block.  Design:
 //
-//   * A workgroup owns WR row blocks x (WT*TW) tokens.  Its raw X tile (all M columns of the current
-//     K span) is staged once in LDS, TRANSPOSED to [input column][token], and shared by all WR row
-//     blocks; the per-row-block gather happens when a wave reads its B operand: each
+//   * X is first re-laid by the staging pass (vnm_stage.hip) into per-(token tile, K step) images
+//     [raw input column][token].  A workgroup owns WR row blocks x 128 tokens and streams the images
+//     of its token tile through a ring of LDS buffers with asynchronous global->LDS copies
+//     (global_load_lds_dwordx4: no registers, no VALU work, fully coalesced).
+//   * The raw image (all M columns of every block) is shared by the WR row blocks of the
+//     workgroup; the per-row-block gather happens when a wave reads its B operand: each
 //     ds_read_b64_tr_b16 fetches, for 16 tokens, the 4 kept columns of one column block -- the rows
 //     are chosen per lane from the packed column table -- and hands every lane the 4 K-consecutive
-//     values of its token.  LDS read traffic is therefore exactly the gathered operand, with no
-//     select arithmetic.
-//   * The transposition is done in registers while staging: a thread loads a 4-token x 8-column
-//     patch with four 16-byte global loads, interleaves halves with v_perm and writes eight 8-byte
-//     LDS rows.
-//   * A wave owns one row block (V rows = V/32 A tiles) x TW tokens (TW/32 B tiles); the A operand
+//     values of its token.  LDS read traffic is exactly the gathered operand; there is no select
+//     arithmetic.
+//   * A wave owns one row block (V rows = V/32 A tiles) x TW tokens (TW/32 B tiles).  Its A operand
 //     (kept values in lane order + 2-bit positions) comes straight from the packed copy in global
-//     memory with one 16-byte load per lane and tile; accumulators stay in registers for the whole
-//     K loop.
+//     memory, one 16-byte load per lane and tile, two K steps ahead; accumulators stay in
+//     registers for the whole K loop.
+#include <type_traits>
+#include <stdlib.h>
 #include "vnm_internal.h"
 
 namespace vnm {
@@ -30,38 +32,195 @@ typedef short s4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 #define VNM_LDS(T) __attribute__((address_space(3))) T*
+#define VNM_GLB(T) __attribute__((address_space(1))) T*
 
-constexpr int kPitchPad = 64;  // bytes: successive staged rows start 16 banks apart
-
-// 16 lanes x 8 bytes in, transposed out: lanes 4j..4j+3 of a 16-lane group address row j (16
-// consecutive fp16 of it), and lane i receives element i of each of the 4 rows.
+// ds_read_b64_tr_b16: 16 lanes x 8 bytes in, transposed out: lanes 4j..4j+3 of a 16-lane group
+// address row j (16 consecutive fp16 of it), and lane i receives element i of each of the 4 rows.
+// Issued through inline assembly on purpose: the compiler must not see these as LDS reads, or it
+// would drain every outstanding asynchronous global->LDS copy (vmcnt(0)) in front of each of them.
+// The matching lgkmcnt waits are therefore written by hand (lds_wait below), tied to the
+// destination registers so that no use can be scheduled ahead of the wait.
+template <int OFF>
 __device__ __forceinline__ h4 lds_read_tr(unsigned byte_addr) {
-  const s4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((VNM_LDS(s4))(size_t)byte_addr);
-  return __builtin_bit_cast(h4, v);
+  h4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(byte_addr), "n"(OFF) : "memory");
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(h4& a, h4& b, h4& c, h4& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
 }
 
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, other counters unconstrained)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_imm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Steady-state K loop for V = 64 (2 A tiles x 4 B tiles per wave), written in assembly.
+//
+// Why assembly: the loop keeps two kinds of vector-memory operations in flight at once -- the
+// register loads of the next A operand and the asynchronous global->LDS copies of the image two
+// steps ahead -- and must wait for the former while the latter keep flying (vmcnt counts both, in
+// order).  Compiled code drains everything (vmcnt(0)) at each use, which serialises the copies with
+// the multiply.  Here every wait is explicit:
+//     top      issue A(s+1) loads, then the NCW copies of image s+2
+//     middle   16 transposing LDS reads (B operand of step s), 8 sparse MFMAs as the tiles land
+//     bottom   s_waitcnt vmcnt(NCW): A(s+1) and the previous iteration's copies (image s+1) are
+//              in, this iteration's copies are not waited for; rotate; s_barrier
+// Temporaries live in fixed registers v192..v249 / s80..s89 (declared clobbered); accumulators and
+// the current A operand are ordinary operands.
+//   v[192:223] B tiles 0..3        v[224:231] A values (cur)   v232 idx (cur)   v233 column table (cur)
+//   v[234:241] A values (next)     v242 idx (next)             v243 column table (next)
+//   v[244:247] B row addresses     v248, v249 scratch
+//   s[80:81] A values ptr  s[82:83] idx ptr  s[84:85] column table ptr  s[86:87] image ptr  s[88:89] copy src
+#define VNM_ASM_COPY(K4096)                                   \
+  "s_add_u32 %[tci], %[woff], " #K4096 "\n"                   \
+  "s_min_u32 %[tci], %[tci], %[clamp]\n"                      \
+  "s_add_u32 s88, s86, %[tci]\n"                              \
+  "s_addc_u32 s89, s87, 0\n"                                  \
+  "s_add_u32 m0, %[wr], %[tci]\n"                             \
+  "s_nop 0\n"                                                 \
+  "global_load_lds_dwordx4 %[voff16], s[88:89]\n"
+#define VNM_ASM_COPIES_3 VNM_ASM_COPY(0) VNM_ASM_COPY(4096) VNM_ASM_COPY(8192)
+#define VNM_ASM_COPIES_4 VNM_ASM_COPIES_3 VNM_ASM_COPY(12288)
+#define VNM_ASM_COPIES_5 VNM_ASM_COPIES_4 VNM_ASM_COPY(16384)
+#define VNM_ASM_COPIES_6 VNM_ASM_COPIES_5 VNM_ASM_COPY(20480)
+#define VNM_ASM_COPIES_7 VNM_ASM_COPIES_6 VNM_ASM_COPY(24576)
+#define VNM_ASM_COPIES_8 VNM_ASM_COPIES_7 VNM_ASM_COPY(28672)
+#define VNM_ASM_COPIES_9 VNM_ASM_COPIES_8 VNM_ASM_COPY(32768)
+#define VNM_ASM_COPIES_10 VNM_ASM_COPIES_9 VNM_ASM_COPY(36864)
+
+#define VNM_ASM_READ4(OFF, R0, R1, R2, R3)                                     \
+  "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v244 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R1 ":" #R1 "+1], v245 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R2 ":" #R2 "+1], v246 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R3 ":" #R3 "+1], v247 offset:" #OFF "\n"
+
+#define VNM_ASM_LOOP_V64(COPIES, NCWSTR)                                                          \
+  asm volatile(                                                                                   \
+      "s_mov_b32 s80, %[pa_lo]\n s_mov_b32 s81, %[pa_hi]\n"                                       \
+      "s_mov_b32 s82, %[pi_lo]\n s_mov_b32 s83, %[pi_hi]\n"                                       \
+      "s_mov_b32 s84, %[pc_lo]\n s_mov_b32 s85, %[pc_hi]\n"                                       \
+      "s_mov_b32 s86, %[xs_lo]\n s_mov_b32 s87, %[xs_hi]\n"                                       \
+      "v_mov_b32 v224, %[c0]\n v_mov_b32 v225, %[c1]\n v_mov_b32 v226, %[c2]\n v_mov_b32 v227, %[c3]\n" \
+      "v_mov_b32 v228, %[c4]\n v_mov_b32 v229, %[c5]\n v_mov_b32 v230, %[c6]\n v_mov_b32 v231, %[c7]\n" \
+      "v_mov_b32 v232, %[cidx]\n v_mov_b32 v233, %[cpc]\n"                                        \
+      "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
+      "1:\n"                                                                                      \
+      /* A operand of step s+1 */                                                                 \
+      "global_load_dwordx4 v[234:237], %[voff16], s[80:81]\n"                                     \
+      "global_load_dwordx4 v[238:241], %[voff16], s[80:81] offset:1024\n"                         \
+      "global_load_dword v242, %[voffi], s[82:83]\n"                                              \
+      "global_load_dword v243, %[voffp], s[84:85]\n"                                              \
+      /* asynchronous copies of image s+2 */                                                      \
+      COPIES                                                                                      \
+      /* B row addresses of step s */                                                             \
+      "v_add_u32 v248, %[rd], %[vtok]\n"                                                          \
+      "v_and_b32 v249, 0xff, v233\n"                                                              \
+      "v_mad_u32_u24 v244, v249, %[pitch], v248\n"                                                \
+      "v_bfe_u32 v249, v233, 8, 8\n"                                                              \
+      "v_mad_u32_u24 v245, v249, %[pitch], v248\n"                                                \
+      "v_bfe_u32 v249, v233, 16, 8\n"                                                             \
+      "v_mad_u32_u24 v246, v249, %[pitch], v248\n"                                                \
+      "v_lshrrev_b32 v249, 24, v233\n"                                                            \
+      "v_mad_u32_u24 v247, v249, %[pitch], v248\n"                                                \
+      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
+      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
+      VNM_ASM_READ4(128, 208, 210, 212, 214)                                                      \
+      VNM_ASM_READ4(192, 216, 218, 220, 222)                                                      \
+      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
+      "v_smfmac_f32_32x32x32_f16 %[a00], v[224:227], v[192:199], v232\n"                          \
+      "v_smfmac_f32_32x32x32_f16 %[a10], v[228:231], v[192:199], v232 abid:1\n"                   \
+      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a01], v[224:227], v[200:207], v232\n"                          \
+      "v_smfmac_f32_32x32x32_f16 %[a11], v[228:231], v[200:207], v232 abid:1\n"                   \
+      "s_waitcnt lgkmcnt(4)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a02], v[224:227], v[208:215], v232\n"                          \
+      "v_smfmac_f32_32x32x32_f16 %[a12], v[228:231], v[208:215], v232 abid:1\n"                   \
+      "s_waitcnt lgkmcnt(0)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a03], v[224:227], v[216:223], v232\n"                          \
+      "v_smfmac_f32_32x32x32_f16 %[a13], v[228:231], v[216:223], v232 abid:1\n"                   \
+      /* rotate ring slots, advance pointers */                                                   \
+      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
+      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
+      "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                                       \
+      "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                                        \
+      "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"                                         \
+      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
+      /* A(s+1) and image s+1 have landed; this iteration's copies stay in flight */              \
+      "s_waitcnt vmcnt(" NCWSTR ")\n"                                                             \
+      "v_mov_b32 v224, v234\n v_mov_b32 v225, v235\n v_mov_b32 v226, v236\n v_mov_b32 v227, v237\n" \
+      "v_mov_b32 v228, v238\n v_mov_b32 v229, v239\n v_mov_b32 v230, v240\n v_mov_b32 v231, v241\n" \
+      "v_mov_b32 v232, v242\n v_mov_b32 v233, v243\n"                                             \
+      "s_barrier\n"                                                                               \
+      "s_sub_u32 %[n], %[n], 1\n"                                                                 \
+      "s_cmp_lg_u32 %[n], 0\n"                                                                    \
+      "s_cbranch_scc1 1b\n"                                                                       \
+      "v_mov_b32 %[c0], v224\n v_mov_b32 %[c1], v225\n v_mov_b32 %[c2], v226\n v_mov_b32 %[c3], v227\n" \
+      "v_mov_b32 %[c4], v228\n v_mov_b32 %[c5], v229\n v_mov_b32 %[c6], v230\n v_mov_b32 %[c7], v231\n" \
+      "v_mov_b32 %[cidx], v232\n v_mov_b32 %[cpc], v233\n"                                        \
+      : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
+        [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
+        [c0] "+v"(cur.w[0].x), [c1] "+v"(cur.w[0].y), [c2] "+v"(cur.w[0].z), [c3] "+v"(cur.w[0].w), \
+        [c4] "+v"(cur.w[1].x), [c5] "+v"(cur.w[1].y), [c6] "+v"(cur.w[1].z), [c7] "+v"(cur.w[1].w), \
+        [cidx] "+v"(cur.idx[0]), [cpc] "+v"(cur.pc4),                                             \
+        [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                       \
+      : [pa_lo] "s"(l_pa_lo), [pa_hi] "s"(l_pa_hi), [pi_lo] "s"(l_pi_lo), [pi_hi] "s"(l_pi_hi),   \
+        [pc_lo] "s"(l_pc_lo), [pc_hi] "s"(l_pc_hi), [xs_lo] "s"(l_xs_lo), [xs_hi] "s"(l_xs_hi),   \
+        [voff16] "v"(l_voff16), [voffi] "v"(l_voffi), [voffp] "v"(l_voffp), [vtok] "v"(tokoff),   \
+        [woff] "s"(l_woff), [clamp] "s"(l_clamp), [pitch] "s"(l_pitch), [img] "s"(l_img),         \
+        [lbeg] "s"(l_lbeg), [lend] "s"(l_lend)                                                    \
+      : "memory", "scc", "m0",                                                                    \
+        "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", \
+        "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", \
+        "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", \
+        "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", \
+        "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249",           \
+        "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89")
+
 struct SpmmArgs {
-  const _Float16* X; int64_t T, ldx;
+  const unsigned char* Xs; int64_t T;
   const uint4* pa; const unsigned short* pidx; const unsigned* pcol;
-  int64_t out, in, R, S;
-  int M, KS;
+  int64_t out, R, S;
+  int M;
+  int image_bytes;   // multiple of 1024
   void* Y; int64_t ldy;
-  int vec_store;   // Y and ldy allow 4-wide stores
+  int vec_store;     // Y and ldy allow 4-wide stores
+  int y_fp32;
 };
 
-template <int V, int TW, int WR, int WT, typename OutT>
+// One K step = 8 column blocks = 8*M raw input columns = 32 compacted K = one staged image.
+// Iteration s of a wave:
+//   1. issue the asynchronous copy of its share of image s+NBUF-1 into ring slot (s+NBUF-1) % NBUF
+//      (the slot read in iteration s-1, free since the barrier that ended it),
+//   2. read the B operand of step s from slot s % NBUF, issue the sparse MFMAs,
+//   3. issue the global loads of the A operand of step s+2,
+//   4. wait until everything it issued before this iteration has landed (its share of image s+1
+//      among it), then one barrier: image s+1 is complete for everybody.
+template <int V, int TW, int WR, int WT, int NCW>
 __global__ void __launch_bounds__(64 * WR * WT)
 spmm_smfmac_kernel(const SpmmArgs a) {
-  constexpr int AT = V / 32, BT = TW / 32, NT = 64 * WR * WT, TT = WT * TW;
-  constexpr int P = TT * 2 + kPitchPad;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int NBUF = 3;
+  constexpr int AT = V / 32, BT = TW / 32, NW = WR * WT;
+  static_assert(WT * TW == kTokTile, "a workgroup spans one staged token tile");
+  static_assert(BT <= 4 && AT <= 4 && NBUF == 3, "tiling assumed by the step body");
+  constexpr int P = kImagePitch;
+  constexpr int NI = (AT + 1) / 2;
+  constexpr int NA = AT + (AT == 1 ? 1 : AT / 2) + 1;     // vector loads of one A-operand fetch
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave / WT, wt = wave % WT;
   const int64_t r = (int64_t)blockIdx.y * WR + wr;
   const bool r_valid = r < a.R;
-  const int64_t t0 = (int64_t)blockIdx.x * TT;
-  const int M = a.M;
+  const int64_t rr = r_valid ? r : a.R - 1;      // out-of-range waves compute a valid row block, store nothing
+  const int64_t t0 = (int64_t)blockIdx.x * kTokTile;
+  const int64_t S = a.S;
+  const int img = a.image_bytes;
+  const int n_ci = img / 1024;                   // wave-wide copies per image; <= NCW * NW
 
   f16v acc[AT][BT];
 #pragma unroll
@@ -76,84 +235,166 @@ spmm_smfmac_kernel(const SpmmArgs a) {
   const unsigned lds0 = (unsigned)(size_t)(VNM_LDS(unsigned char))smem;
   const unsigned tokoff = (unsigned)((wt * TW + tg * 16 + q * 4) * 2);
 
-  constexpr int NPT = TT / 4;  // 4-token patches along the token axis
-  for (int64_t s0 = 0; s0 < a.S; s0 += a.KS) {
-    const int nks = (int)((a.S - s0) < a.KS ? (a.S - s0) : a.KS);
-    // ---- stage the raw X tile, transposed
-    const int npc = nks * M;                                       // 8-column patches
-    const int64_t col0 = s0 * 8 * M;
-    for (int item = tid; item < npc * NPT; item += NT) {
-      const int pt = item % NPT, pc = item / NPT;
-      const int64_t col = col0 + pc * 8;
-      const int64_t tok = t0 + 4 * pt;
-      uint4 g[4];
+  const unsigned char* xs_tile = a.Xs + (int64_t)blockIdx.x * S * img;
+  // copy this wave's share of image s into ring slot `slot`; chunks beyond the image are clamped to
+  // its last chunk (an idempotent duplicate) so that every wave issues exactly NCW copies and the
+  // loop body stays straight-line code with a known number of outstanding operations
+  auto copy_image = [&](int64_t s, int slot) {
+    const unsigned char* src = xs_tile + s * img + lane * 16;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        g[j] = make_uint4(0, 0, 0, 0);
-        if (col < a.in && tok + j < a.T) g[j] = *(const uint4*)(a.X + (tok + j) * a.ldx + col);
-      }
-      unsigned char* dst = smem + (size_t)(pc * 8) * P + pt * 8;
-      const unsigned d[4][4] = {{g[0].x, g[1].x, g[2].x, g[3].x}, {g[0].y, g[1].y, g[2].y, g[3].y},
-                                {g[0].z, g[1].z, g[2].z, g[3].z}, {g[0].w, g[1].w, g[2].w, g[3].w}};
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        uint2 lo, hi;
-        lo.x = __builtin_amdgcn_perm(d[p][1], d[p][0], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(d[p][3], d[p][2], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(d[p][1], d[p][0], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(d[p][3], d[p][2], 0x07060302u);
-        *(uint2*)(dst + (size_t)(2 * p) * P) = lo;
-        *(uint2*)(dst + (size_t)(2 * p + 1) * P) = hi;
-      }
+    for (int k = 0; k < NCW; ++k) {
+      int ci = wave + k * NW;
+      ci = ci < n_ci ? ci : n_ci - 1;
+      __builtin_amdgcn_global_load_lds((VNM_GLB(void))(src + ci * 1024),
+                                       (VNM_LDS(void))(smem + slot * img + ci * 1024), 16, 0, 0);
     }
-    __syncthreads();
-    // ---- multiply
-    if (r_valid) {
-      for (int ks = 0; ks < nks; ++ks) {
-        const int64_t rs = r * a.S + s0 + ks;
-        h8 av[AT];
+  };
+
+  // A operand of one K step as it sits in registers
+  struct AOp { uint4 w[AT]; unsigned idx[NI]; unsigned pc4; };
+  const uint4* pa_w = a.pa + rr * S * AT * 64 + lane;
+  const unsigned* pidx_w = (const unsigned*)a.pidx;      // AT >= 2: AT/2 dwords per lane and step
+  const unsigned* pcol_w = a.pcol + rr * S * 8 + hB * 4 + kq;
+  auto load_a = [&](AOp& o, int64_t s) {
 #pragma unroll
-        for (int i = 0; i < AT; ++i) {
-          const uint4 w = a.pa[(rs * AT + i) * 64 + lane];
-          av[i] = __builtin_bit_cast(h8, w);
-        }
-        unsigned idxw[(AT + 1) / 2];
-        if (AT == 1) idxw[0] = a.pidx[rs * 64 + lane];
-        else {
+    for (int i = 0; i < AT; ++i) o.w[i] = pa_w[(s * AT + i) * 64];
+    if (AT == 1) o.idx[0] = a.pidx[(rr * S + s) * 64 + lane];
+    else {
 #pragma unroll
-          for (int i = 0; i < AT / 2; ++i) idxw[i] = ((const unsigned*)a.pidx)[(rs * 64 + lane) * (AT / 2) + i];
-        }
-        const unsigned pc4 = a.pcol[rs * 8 + hB * 4 + kq];
-        unsigned addr[4];
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-          addr[m] = lds0 + (unsigned)(ks * 8 * M + ((pc4 >> (8 * m)) & 255u)) * P + tokoff;
-#pragma unroll
-        for (int j = 0; j < BT; ++j) {
-          const h4 b0 = lds_read_tr(addr[0] + j * 64);
-          const h4 b1 = lds_read_tr(addr[1] + j * 64);
-          const h4 b2 = lds_read_tr(addr[2] + j * 64);
-          const h4 b3 = lds_read_tr(addr[3] + j * 64);
-          h16 bv;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { bv[e] = b0[e]; bv[4 + e] = b1[e]; bv[8 + e] = b2[e]; bv[12 + e] = b3[e]; }
-#pragma unroll
-          for (int i = 0; i < AT; ++i) {
-            if (i & 1)
-              acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], (int)idxw[i / 2], 0, 1);
-            else
-              acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], (int)idxw[i / 2], 0, 0);
-          }
-        }
-      }
+      for (int i = 0; i < AT / 2; ++i) o.idx[i] = pidx_w[((rr * S + s) * 64 + lane) * (AT / 2) + i];
     }
-    __syncthreads();
+    o.pc4 = pcol_w[s * 8];
+  };
+
+  int slot = 0;        // ring slot of step s
+  AOp cur, nxt;
+  // Iteration s.  FULL: steady state (s + 2 < S), everything is issued unconditionally so that the
+  // body is straight-line code with a known number of outstanding vector-memory operations.
+  //   1. fetch the A operand of step s+1 (registers)
+  //   2. issue the asynchronous copy of this wave's share of image s+2 into the slot read in s-1
+  //   3. read the B operand of step s from LDS, issue the sparse MFMAs
+  //   4. wait until only the copies of (2) are outstanding -- image s+1 and A(s+1) have landed --
+  //      then one barrier: image s+1 is complete for every wave
+  auto step = [&](auto fullc, int64_t s) {
+    constexpr bool FULL = decltype(fullc)::value;
+    if (FULL || s + 1 < S) load_a(nxt, s + 1);
+    if (FULL || s + 2 < S) {
+      int cs = slot + 2; cs = cs >= NBUF ? cs - NBUF : cs;
+      copy_image(s + 2, cs);
+    }
+    unsigned addr[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+      addr[m] = lds0 + slot * img + ((cur.pc4 >> (8 * m)) & 255u) * P + tokoff;
+    h8 av[AT];
+#pragma unroll
+    for (int i = 0; i < AT; ++i) av[i] = __builtin_bit_cast(h8, cur.w[i]);
+    const int idx0 = (int)cur.idx[0];
+    const int idx1 = (int)cur.idx[NI - 1];
+    h4 b[BT][4];
+    // all B reads of the step first (LDS returns in order), then per tile: wait, multiply
+#define VNM_RD(j) { b[j][0] = lds_read_tr<(j) * 64>(addr[0]); b[j][1] = lds_read_tr<(j) * 64>(addr[1]); \
+                    b[j][2] = lds_read_tr<(j) * 64>(addr[2]); b[j][3] = lds_read_tr<(j) * 64>(addr[3]); }
+    VNM_RD(0)
+    if (BT > 1) VNM_RD(1 % BT)
+    if (BT > 2) VNM_RD(2 % BT)
+    if (BT > 3) VNM_RD(3 % BT)
+#undef VNM_RD
+    __builtin_amdgcn_sched_barrier(0);
+#define VNM_MM(j) {                                                                              \
+      lds_wait<4 * (BT - 1 - (j))>(b[j][0], b[j][1], b[j][2], b[j][3]);                          \
+      h16 bv;                                                                                    \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                            \
+        bv[e] = b[j][0][e]; bv[4 + e] = b[j][1][e]; bv[8 + e] = b[j][2][e]; bv[12 + e] = b[j][3][e]; } \
+      _Pragma("unroll") for (int i = 0; i < AT; ++i) {                                           \
+        const int ix = (i / 2 == 0) ? idx0 : idx1;                                               \
+        if (i & 1) acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], ix, 0, 1); \
+        else acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], ix, 0, 0); } \
+      __builtin_amdgcn_sched_barrier(0); }
+    VNM_MM(0)
+    if (BT > 1) VNM_MM(1 % BT)
+    if (BT > 2) VNM_MM(2 % BT)
+    if (BT > 3) VNM_MM(3 % BT)
+#undef VNM_MM
+    if (FULL) wait_vmcnt_imm<NCW>(); else wait_vmcnt_imm<0>();
+    // Make the fetched A operand "used" right here, inside this straight-line block, so that the
+    // compiler's own wait for it is the exact vmcnt(NCW) above and not a conservative vmcnt(0) at
+    // the loop head (which would also drain the copies that are meant to stay in flight).
+    if (FULL || s + 1 < S) {
+#pragma unroll
+      for (int i = 0; i < AT; ++i)
+        asm volatile("" : "+v"(nxt.w[i].x), "+v"(nxt.w[i].y), "+v"(nxt.w[i].z), "+v"(nxt.w[i].w));
+#pragma unroll
+      for (int i = 0; i < NI; ++i) asm volatile("" : "+v"(nxt.idx[i]));
+      asm volatile("" : "+v"(nxt.pc4));
+    }
+    __builtin_amdgcn_s_barrier();
+    slot = slot + 1 == NBUF ? 0 : slot + 1;
+    cur = nxt;
+  };
+
+  using Full = std::true_type;
+  using Tail = std::false_type;
+  for (int k = 0; k < NBUF - 1 && k < S; ++k) copy_image(k, k);
+  load_a(cur, 0);
+  wait_vmcnt_imm<0>();
+  __builtin_amdgcn_s_barrier();
+  int64_t s = 0;
+  if constexpr (V == 64 && TW == 128) {
+    // steady state (s + 2 < S) in assembly; s stays 0 here, so `cur` holds A(0), slot 0 is read first
+    if (S > 2) {
+      const uint64_t pa_p = (uint64_t)(a.pa + (rr * S + 1) * AT * 64);
+      const uint64_t pi_p = (uint64_t)(a.pidx + (rr * S + 1) * 64 * AT);
+      const uint64_t pc_p = (uint64_t)(a.pcol + (rr * S + 1) * 8);
+      const uint64_t xs_p = (uint64_t)(xs_tile + 2 * (int64_t)img);
+      unsigned l_pa_lo = __builtin_amdgcn_readfirstlane((unsigned)pa_p), l_pa_hi = __builtin_amdgcn_readfirstlane((unsigned)(pa_p >> 32));
+      unsigned l_pi_lo = __builtin_amdgcn_readfirstlane((unsigned)pi_p), l_pi_hi = __builtin_amdgcn_readfirstlane((unsigned)(pi_p >> 32));
+      unsigned l_pc_lo = __builtin_amdgcn_readfirstlane((unsigned)pc_p), l_pc_hi = __builtin_amdgcn_readfirstlane((unsigned)(pc_p >> 32));
+      unsigned l_xs_lo = __builtin_amdgcn_readfirstlane((unsigned)xs_p), l_xs_hi = __builtin_amdgcn_readfirstlane((unsigned)(xs_p >> 32));
+      unsigned l_voff16 = lane * 16, l_voffi = lane * 4, l_voffp = (hB * 4 + kq) * 4;
+      unsigned l_woff = wave * 1024, l_clamp = (n_ci - 1) * 1024, l_pitch = P, l_img = img;
+      unsigned l_lbeg = __builtin_amdgcn_readfirstlane(lds0), l_lend = l_lbeg + 3 * img;
+      unsigned l_rd = l_lbeg, l_wr = l_lbeg + 2 * img, l_n = (unsigned)(S - 2), l_tci;
+      const unsigned tokoff_rel = tokoff;   // LDS base is carried by rd
+      {
+        const unsigned tokoff = tokoff_rel;
+        if constexpr (NCW == 3) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_3, "3");
+        else if constexpr (NCW == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_4, "4");
+        else if constexpr (NCW == 5) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_5, "5");
+        else if constexpr (NCW == 6) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_6, "6");
+        else if constexpr (NCW == 7) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_7, "7");
+        else if constexpr (NCW == 8) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_8, "8");
+        else if constexpr (NCW == 9) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_9, "9");
+        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES_10, "10");
+      }
+      s = S - 2;
+      slot = (int)(s % NBUF);
+    }
+  } else {
+    for (; s + 2 < S; ++s) step(Full{}, s);
   }
+  for (; s < S; ++s) step(Tail{}, s);
 
   // ---- epilogue: lane holds, per (A tile, B tile, jq), 4 consecutive output channels of one token
   if (!r_valid) return;
-  OutT* Y = (OutT*)a.Y;
   const int tokl = lane & 31;
+  auto store4 = [&](auto* dst, int64_t o, float v0, float v1, float v2, float v3) {
+    using OutT = std::remove_pointer_t<decltype(dst)>;
+    if (a.vec_store && o + 3 < a.out) {
+      if (sizeof(OutT) == 2) {
+        h4 pk = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+        *(h4*)dst = pk;
+      } else {
+        f4 pk = {v0, v1, v2, v3};
+        *(f4*)dst = pk;
+      }
+    } else {
+      if (o < a.out) dst[0] = (OutT)v0;
+      if (o + 1 < a.out) dst[1] = (OutT)v1;
+      if (o + 2 < a.out) dst[2] = (OutT)v2;
+      if (o + 3 < a.out) dst[3] = (OutT)v3;
+    }
+  };
 #pragma unroll
   for (int j = 0; j < BT; ++j) {
     const int64_t tok = t0 + wt * TW + j * 32 + tokl;
@@ -163,23 +404,10 @@ spmm_smfmac_kernel(const SpmmArgs a) {
 #pragma unroll
       for (int jq = 0; jq < 4; ++jq) {
         const int64_t o = r * V + i * 32 + 8 * jq + 4 * hB;
-        OutT* dst = Y + tok * a.ldy + o;
         const float v0 = acc[i][j][4 * jq], v1 = acc[i][j][4 * jq + 1], v2 = acc[i][j][4 * jq + 2],
                     v3 = acc[i][j][4 * jq + 3];
-        if (a.vec_store && o + 3 < a.out) {
-          if (sizeof(OutT) == 2) {
-            h4 pk = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
-            *(h4*)dst = pk;
-          } else {
-            f4 pk = {v0, v1, v2, v3};
-            *(f4*)dst = pk;
-          }
-        } else {
-          if (o < a.out) dst[0] = (OutT)v0;
-          if (o + 1 < a.out) dst[1] = (OutT)v1;
-          if (o + 2 < a.out) dst[2] = (OutT)v2;
-          if (o + 3 < a.out) dst[3] = (OutT)v3;
-        }
+        if (a.y_fp32) store4((float*)a.Y + tok * a.ldy + o, o, v0, v1, v2, v3);
+        else store4((_Float16*)a.Y + tok * a.ldy + o, o, v0, v1, v2, v3);
       }
     }
   }
@@ -189,48 +417,60 @@ bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d) {
   return has_packed(d.V, d.M) && d.in % 8 == 0 && ldx % 8 == 0 && ((uintptr_t)X & 15) == 0;
 }
 
-template <int V, int TW, int WR, int WT, typename OutT>
+template <int V, int TW, int WR, int WT, int NCW>
 static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
-  constexpr int TT = WT * TW;
-  constexpr int P = TT * 2 + kPitchPad;
-  const size_t lds = (size_t)a.KS * 8 * a.M * P;
-  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, OutT>;
+  const size_t lds = (size_t)3 * a.image_bytes;
+  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(spmm_smfmac)"); return VNM_ERR_HIP; }
     attr_set = true;
   }
-  dim3 grid((unsigned)((a.T + TT - 1) / TT), (unsigned)((a.R + WR - 1) / WR));
+  dim3 grid((unsigned)((a.T + kTokTile - 1) / kTokTile), (unsigned)((a.R + WR - 1) / WR));
   hipLaunchKernelGGL(kern, grid, dim3(64 * WR * WT), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_smfmac_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
 }
 
-int launch_spmm_smfmac(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+// NCW = wave-wide 1 KiB copies per wave and image = ceil(image KiB / waves per workgroup)
+template <int V, int TW, int WR, int WT>
+static int launch_by_ncw(const SpmmArgs& a, hipStream_t st) {
+  const int ncw = (a.image_bytes / 1024 + WR * WT - 1) / (WR * WT);
+  switch (ncw) {
+    case 2: return launch_cfg<V, TW, WR, WT, 2>(a, st);
+    case 3: return launch_cfg<V, TW, WR, WT, 3>(a, st);
+    case 4: return launch_cfg<V, TW, WR, WT, 4>(a, st);
+    case 5: return launch_cfg<V, TW, WR, WT, 5>(a, st);
+    case 6: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 6 : 2)>(a, st); break;
+    case 7: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 7 : 2)>(a, st); break;
+    case 8: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 8 : 2)>(a, st); break;
+    case 9: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 9 : 2)>(a, st); break;
+    case 10: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 10 : 2)>(a, st); break;
+  }
+  return VNM_ERR_UNSUPPORTED;
+}
+
+int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
   SpmmArgs a;
-  a.X = (const _Float16*)X; a.T = T; a.ldx = ldx;
+  a.Xs = (const unsigned char*)Xs; a.T = T;
   a.pa = (const uint4*)(p + pl.pa_off);
   a.pidx = (const unsigned short*)(p + pl.pidx_off);
   a.pcol = (const unsigned*)(p + pl.pcol_off);
-  a.out = d.out; a.in = d.in; a.R = d.R; a.S = d.S; a.M = d.M;
-  a.KS = 128 / (8 * d.M) > 0 ? 128 / (8 * d.M) : 1;
-  a.Y = Y; a.ldy = ldy;
+  a.out = d.out; a.R = d.R; a.S = d.S; a.M = d.M;
+  a.image_bytes = (int)image_bytes(d.M);
+  a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.vec_store = (ldy % 4 == 0) && (((uintptr_t)Y & (y_dtype == 0 ? 7 : 15)) == 0);
-  if (T > (int64_t)65535 * 128) return VNM_ERR_UNSUPPORTED;
-#define VNM_GO(Vv, TWv, WRv, WTv)                                                       \
-  return y_dtype == 0 ? launch_cfg<Vv, TWv, WRv, WTv, _Float16>(a, st)                 \
-                      : launch_cfg<Vv, TWv, WRv, WTv, float>(a, st)
+  if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (d.R + 3) / 4 > 65535) return VNM_ERR_UNSUPPORTED;
   switch (d.V) {
-    case 32: VNM_GO(32, 256, 4, 1);
-    case 64: VNM_GO(64, 128, 4, 1);
-    case 128: VNM_GO(128, 64, 4, 1);
+    case 32: return launch_by_ncw<32, 128, 8, 1>(a, st);
+    case 64: return launch_by_ncw<64, 128, 4, 1>(a, st);
+    case 128: return launch_by_ncw<128, 64, 2, 2>(a, st);
   }
-#undef VNM_GO
   return VNM_ERR_UNSUPPORTED;
 }
 

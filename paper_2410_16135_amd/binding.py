@@ -25,7 +25,8 @@ class VnmSizes(ctypes.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_PKG_DIR, "libvnm.so")
+    """In-tree library; VNM_LIB_PATH overrides it (developer aid for A/B-testing kernel builds)."""
+    return os.environ.get("VNM_LIB_PATH") or os.path.join(_PKG_DIR, "libvnm.so")
 
 
 def load_library():

@@ -17,8 +17,10 @@
 //     arithmetic.
 //   * A wave owns one row block (V rows = V/32 A tiles) x TW tokens (TW/32 B tiles).  Its A operand
 //     (kept values in lane order + 2-bit positions) comes straight from the packed copy in global
-//     memory, one 16-byte load per lane and tile, two K steps ahead; accumulators stay in
-//     registers for the whole K loop.
+//     memory, one 16-byte load per lane and tile; accumulators stay in registers for the whole K
+//     loop.
+//   * For V = 64 the steady-state K loop is written in assembly (see below); other V use a
+//     compiler-scheduled loop that drains memory every step.
 #include <type_traits>
 #include <stdlib.h>
 #include "vnm_internal.h"
@@ -50,8 +52,6 @@ template <int N>
 __device__ __forceinline__ void lds_wait(h4& a, h4& b, h4& c, h4& d) {
   asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
 }
-
-// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, other counters unconstrained)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_imm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
@@ -61,20 +61,24 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
 // Steady-state K loop for V = 64 (2 A tiles x 4 B tiles per wave), written in assembly.
 //
 // Why assembly: the loop keeps two kinds of vector-memory operations in flight at once -- the
-// register loads of the next A operand and the asynchronous global->LDS copies of the image two
-// steps ahead -- and must wait for the former while the latter keep flying (vmcnt counts both, in
-// order).  Compiled code drains everything (vmcnt(0)) at each use, which serialises the copies with
-// the multiply.  Here every wait is explicit:
-//     top      issue A(s+1) loads, then the NCW copies of image s+2
-//     middle   16 transposing LDS reads (B operand of step s), 8 sparse MFMAs as the tiles land
-//     bottom   s_waitcnt vmcnt(NCW): A(s+1) and the previous iteration's copies (image s+1) are
-//              in, this iteration's copies are not waited for; rotate; s_barrier
-// Temporaries live in fixed registers v192..v249 / s80..s89 (declared clobbered); accumulators and
-// the current A operand are ordinary operands.
-//   v[192:223] B tiles 0..3        v[224:231] A values (cur)   v232 idx (cur)   v233 column table (cur)
-//   v[234:241] A values (next)     v242 idx (next)             v243 column table (next)
-//   v[244:247] B row addresses     v248, v249 scratch
-//   s[80:81] A values ptr  s[82:83] idx ptr  s[84:85] column table ptr  s[86:87] image ptr  s[88:89] copy src
+// register loads of the A operand two steps ahead and the asynchronous global->LDS copies of the
+// image NBUF-1 steps ahead -- and must wait for the older ones while the younger ones keep flying
+// (vmcnt counts both, in issue order).  Compiled code drains everything (vmcnt(0)) at each use,
+// which serialises the copies with the multiply.  Here every wait is explicit.  Iteration s:
+//     16 transposing LDS reads (B operand of step s, ring slot s % NBUF)
+//     issue the A loads of step s+2 into the register set freed by step s-1
+//     8 sparse MFMAs as the B tiles land, with the NCW copies of image s+NBUF-1 and the scalar
+//         bookkeeping issued underneath them
+//     s_waitcnt vmcnt(VMW): everything older than {this step's loads and copies, the previous
+//         step's copies} has landed, i.e. A(s+1) and image s+1; s_barrier
+// The body is unrolled three times so that the three A register sets rotate by name.
+// Fixed registers (declared clobbered):
+//   v[186:189] B row addresses, v190 v191 scratch, v[192:223] B tiles 0..3,
+//   A sets {values tile 0, values tile 1, index word, column table}:
+//     set0 v[224:227] v[228:231] v232 v233, set1 v[234:237] v[238:241] v242 v243,
+//     set2 v[244:247] v[248:251] v252 v253
+//   s[80:81] A values ptr, s[82:83] index ptr, s[84:85] column table ptr, s[86:87] image ptr,
+//   s[88:89] copy source
 #define VNM_ASM_COPY(K4096)                                   \
   "s_add_u32 %[tci], %[woff], " #K4096 "\n"                   \
   "s_min_u32 %[tci], %[tci], %[clamp]\n"                      \
@@ -93,91 +97,91 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
 #define VNM_ASM_COPIES_10 VNM_ASM_COPIES_9 VNM_ASM_COPY(36864)
 
 #define VNM_ASM_READ4(OFF, R0, R1, R2, R3)                                     \
-  "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v244 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R1 ":" #R1 "+1], v245 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R2 ":" #R2 "+1], v246 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R3 ":" #R3 "+1], v247 offset:" #OFF "\n"
+  "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v186 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R1 ":" #R1 "+1], v187 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R2 ":" #R2 "+1], v188 offset:" #OFF "\n"            \
+  "ds_read_b64_tr_b16 v[" #R3 ":" #R3 "+1], v189 offset:" #OFF "\n"
 
-#define VNM_ASM_LOOP_V64(COPIES, NCWSTR)                                                          \
+#define VNM_ASM_LOAD_A(W0, W1, IDX, PC)                                        \
+  "global_load_dwordx4 v[" W0 "], %[voff16], s[80:81]\n"                       \
+  "global_load_dwordx4 v[" W1 "], %[voff16], s[80:81] offset:1024\n"           \
+  "global_load_dword v" IDX ", %[voffi], s[82:83]\n"                           \
+  "global_load_dword v" PC ", %[voffp], s[84:85]\n"                            \
+  "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                        \
+  "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                         \
+  "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"
+
+// one K step: current A set (CW0, CW1, CIDX, CPC), A set to load (LW0, LW1, LIDX, LPC)
+#define VNM_ASM_STEP(CW0, CW1, CIDX, CPC, LW0, LW1, LIDX, LPC, COPIES, VMWSTR)                     \
+      "v_add_u32 v190, %[rd], %[vtok]\n"                                                          \
+      "v_and_b32 v191, 0xff, v" CPC "\n"                                                          \
+      "v_mad_u32_u24 v186, v191, %[pitch], v190\n"                                                \
+      "v_bfe_u32 v191, v" CPC ", 8, 8\n"                                                          \
+      "v_mad_u32_u24 v187, v191, %[pitch], v190\n"                                                \
+      "v_bfe_u32 v191, v" CPC ", 16, 8\n"                                                         \
+      "v_mad_u32_u24 v188, v191, %[pitch], v190\n"                                                \
+      "v_lshrrev_b32 v191, 24, v" CPC "\n"                                                        \
+      "v_mad_u32_u24 v189, v191, %[pitch], v190\n"                                                \
+      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
+      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
+      VNM_ASM_READ4(128, 208, 210, 212, 214)                                                      \
+      VNM_ASM_READ4(192, 216, 218, 220, 222)                                                      \
+      VNM_ASM_LOAD_A(LW0, LW1, LIDX, LPC)                                                         \
+      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
+      "v_smfmac_f32_32x32x32_f16 %[a00], v[" CW0 "], v[192:199], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a10], v[" CW1 "], v[192:199], v" CIDX " abid:1\n"              \
+      COPIES                                                                                      \
+      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a01], v[" CW0 "], v[200:207], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a11], v[" CW1 "], v[200:207], v" CIDX " abid:1\n"              \
+      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
+      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
+      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
+      "s_waitcnt lgkmcnt(4)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a02], v[" CW0 "], v[208:215], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a12], v[" CW1 "], v[208:215], v" CIDX " abid:1\n"              \
+      "s_waitcnt lgkmcnt(0)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a03], v[" CW0 "], v[216:223], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a13], v[" CW1 "], v[216:223], v" CIDX " abid:1\n"              \
+      "s_waitcnt vmcnt(" VMWSTR ")\n"                                                             \
+      "s_barrier\n"                                                                               \
+      "s_sub_u32 %[n], %[n], 1\n"                                                                 \
+      "s_cmp_eq_u32 %[n], 0\n"                                                                    \
+      "s_cbranch_scc1 9f\n"
+
+#define VNM_ASM_LOOP_V64(COPIES, VMWSTR)                                                          \
   asm volatile(                                                                                   \
       "s_mov_b32 s80, %[pa_lo]\n s_mov_b32 s81, %[pa_hi]\n"                                       \
       "s_mov_b32 s82, %[pi_lo]\n s_mov_b32 s83, %[pi_hi]\n"                                       \
       "s_mov_b32 s84, %[pc_lo]\n s_mov_b32 s85, %[pc_hi]\n"                                       \
       "s_mov_b32 s86, %[xs_lo]\n s_mov_b32 s87, %[xs_hi]\n"                                       \
-      "v_mov_b32 v224, %[c0]\n v_mov_b32 v225, %[c1]\n v_mov_b32 v226, %[c2]\n v_mov_b32 v227, %[c3]\n" \
-      "v_mov_b32 v228, %[c4]\n v_mov_b32 v229, %[c5]\n v_mov_b32 v230, %[c6]\n v_mov_b32 v231, %[c7]\n" \
-      "v_mov_b32 v232, %[cidx]\n v_mov_b32 v233, %[cpc]\n"                                        \
+      VNM_ASM_LOAD_A("224:227", "228:231", "232", "233")                                          \
+      VNM_ASM_LOAD_A("234:237", "238:241", "242", "243")                                          \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
       "1:\n"                                                                                      \
-      /* A operand of step s+1 */                                                                 \
-      "global_load_dwordx4 v[234:237], %[voff16], s[80:81]\n"                                     \
-      "global_load_dwordx4 v[238:241], %[voff16], s[80:81] offset:1024\n"                         \
-      "global_load_dword v242, %[voffi], s[82:83]\n"                                              \
-      "global_load_dword v243, %[voffp], s[84:85]\n"                                              \
-      /* asynchronous copies of image s+2 */                                                      \
-      COPIES                                                                                      \
-      /* B row addresses of step s */                                                             \
-      "v_add_u32 v248, %[rd], %[vtok]\n"                                                          \
-      "v_and_b32 v249, 0xff, v233\n"                                                              \
-      "v_mad_u32_u24 v244, v249, %[pitch], v248\n"                                                \
-      "v_bfe_u32 v249, v233, 8, 8\n"                                                              \
-      "v_mad_u32_u24 v245, v249, %[pitch], v248\n"                                                \
-      "v_bfe_u32 v249, v233, 16, 8\n"                                                             \
-      "v_mad_u32_u24 v246, v249, %[pitch], v248\n"                                                \
-      "v_lshrrev_b32 v249, 24, v233\n"                                                            \
-      "v_mad_u32_u24 v247, v249, %[pitch], v248\n"                                                \
-      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
-      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
-      VNM_ASM_READ4(128, 208, 210, 212, 214)                                                      \
-      VNM_ASM_READ4(192, 216, 218, 220, 222)                                                      \
-      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
-      "v_smfmac_f32_32x32x32_f16 %[a00], v[224:227], v[192:199], v232\n"                          \
-      "v_smfmac_f32_32x32x32_f16 %[a10], v[228:231], v[192:199], v232 abid:1\n"                   \
-      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
-      "v_smfmac_f32_32x32x32_f16 %[a01], v[224:227], v[200:207], v232\n"                          \
-      "v_smfmac_f32_32x32x32_f16 %[a11], v[228:231], v[200:207], v232 abid:1\n"                   \
-      "s_waitcnt lgkmcnt(4)\n s_nop 1\n"                                                          \
-      "v_smfmac_f32_32x32x32_f16 %[a02], v[224:227], v[208:215], v232\n"                          \
-      "v_smfmac_f32_32x32x32_f16 %[a12], v[228:231], v[208:215], v232 abid:1\n"                   \
-      "s_waitcnt lgkmcnt(0)\n s_nop 1\n"                                                          \
-      "v_smfmac_f32_32x32x32_f16 %[a03], v[224:227], v[216:223], v232\n"                          \
-      "v_smfmac_f32_32x32x32_f16 %[a13], v[228:231], v[216:223], v232 abid:1\n"                   \
-      /* rotate ring slots, advance pointers */                                                   \
-      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
-      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
-      "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                                       \
-      "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                                        \
-      "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"                                         \
-      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
-      /* A(s+1) and image s+1 have landed; this iteration's copies stay in flight */              \
-      "s_waitcnt vmcnt(" NCWSTR ")\n"                                                             \
-      "v_mov_b32 v224, v234\n v_mov_b32 v225, v235\n v_mov_b32 v226, v236\n v_mov_b32 v227, v237\n" \
-      "v_mov_b32 v228, v238\n v_mov_b32 v229, v239\n v_mov_b32 v230, v240\n v_mov_b32 v231, v241\n" \
-      "v_mov_b32 v232, v242\n v_mov_b32 v233, v243\n"                                             \
+      VNM_ASM_STEP("224:227", "228:231", "232", "233", "244:247", "248:251", "252", "253", COPIES, VMWSTR) \
+      VNM_ASM_STEP("234:237", "238:241", "242", "243", "224:227", "228:231", "232", "233", COPIES, VMWSTR) \
+      VNM_ASM_STEP("244:247", "248:251", "252", "253", "234:237", "238:241", "242", "243", COPIES, VMWSTR) \
+      "s_branch 1b\n"                                                                             \
+      "9:\n"                                                                                      \
+      "s_waitcnt vmcnt(0)\n"                                                                      \
       "s_barrier\n"                                                                               \
-      "s_sub_u32 %[n], %[n], 1\n"                                                                 \
-      "s_cmp_lg_u32 %[n], 0\n"                                                                    \
-      "s_cbranch_scc1 1b\n"                                                                       \
-      "v_mov_b32 %[c0], v224\n v_mov_b32 %[c1], v225\n v_mov_b32 %[c2], v226\n v_mov_b32 %[c3], v227\n" \
-      "v_mov_b32 %[c4], v228\n v_mov_b32 %[c5], v229\n v_mov_b32 %[c6], v230\n v_mov_b32 %[c7], v231\n" \
-      "v_mov_b32 %[cidx], v232\n v_mov_b32 %[cpc], v233\n"                                        \
       : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
         [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
-        [c0] "+v"(cur.w[0].x), [c1] "+v"(cur.w[0].y), [c2] "+v"(cur.w[0].z), [c3] "+v"(cur.w[0].w), \
-        [c4] "+v"(cur.w[1].x), [c5] "+v"(cur.w[1].y), [c6] "+v"(cur.w[1].z), [c7] "+v"(cur.w[1].w), \
-        [cidx] "+v"(cur.idx[0]), [cpc] "+v"(cur.pc4),                                             \
-        [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                       \
+        [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                    \
       : [pa_lo] "s"(l_pa_lo), [pa_hi] "s"(l_pa_hi), [pi_lo] "s"(l_pi_lo), [pi_hi] "s"(l_pi_hi),   \
         [pc_lo] "s"(l_pc_lo), [pc_hi] "s"(l_pc_hi), [xs_lo] "s"(l_xs_lo), [xs_hi] "s"(l_xs_hi),   \
-        [voff16] "v"(l_voff16), [voffi] "v"(l_voffi), [voffp] "v"(l_voffp), [vtok] "v"(tokoff),   \
+        [voff16] "v"(l_voff16), [voffi] "v"(l_voffi), [voffp] "v"(l_voffp), [vtok] "v"(l_vtok),   \
         [woff] "s"(l_woff), [clamp] "s"(l_clamp), [pitch] "s"(l_pitch), [img] "s"(l_img),         \
         [lbeg] "s"(l_lbeg), [lend] "s"(l_lend)                                                    \
       : "memory", "scc", "m0",                                                                    \
+        "v186", "v187", "v188", "v189", "v190", "v191",                                           \
         "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", \
         "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", \
         "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", \
         "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", \
-        "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249",           \
+        "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", \
+        "v252", "v253",                                                                           \
         "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89")
 
 struct SpmmArgs {
@@ -188,27 +192,22 @@ struct SpmmArgs {
   int image_bytes;   // multiple of 1024
   void* Y; int64_t ldy;
   int vec_store;     // Y and ldy allow 4-wide stores
+  int wide_store;    // fp16 Y: 16-byte aligned base and ldy % 8 == 0 (LDS-transposed epilogue)
   int y_fp32;
 };
 
 // One K step = 8 column blocks = 8*M raw input columns = 32 compacted K = one staged image.
-// Iteration s of a wave:
-//   1. issue the asynchronous copy of its share of image s+NBUF-1 into ring slot (s+NBUF-1) % NBUF
-//      (the slot read in iteration s-1, free since the barrier that ended it),
-//   2. read the B operand of step s from slot s % NBUF, issue the sparse MFMAs,
-//   3. issue the global loads of the A operand of step s+2,
-//   4. wait until everything it issued before this iteration has landed (its share of image s+1
-//      among it), then one barrier: image s+1 is complete for everybody.
-template <int V, int TW, int WR, int WT, int NCW>
+// NCW: wave-wide 1 KiB copies per wave and image (V = 64 assembly loop; 0 elsewhere).
+// NBUF: depth of the LDS image ring.
+template <int V, int TW, int WR, int WT, int NCW, int NBUF>
 __global__ void __launch_bounds__(64 * WR * WT)
 spmm_smfmac_kernel(const SpmmArgs a) {
-  constexpr int NBUF = 3;
   constexpr int AT = V / 32, BT = TW / 32, NW = WR * WT;
   static_assert(WT * TW == kTokTile, "a workgroup spans one staged token tile");
-  static_assert(BT <= 4 && AT <= 4 && NBUF == 3, "tiling assumed by the step body");
+  static_assert(BT <= 4 && AT <= 4, "tiling assumed by the step body");
   constexpr int P = kImagePitch;
   constexpr int NI = (AT + 1) / 2;
-  constexpr int NA = AT + (AT == 1 ? 1 : AT / 2) + 1;     // vector loads of one A-operand fetch
+  constexpr bool kAsmLoop = (V == 64 && TW == 128 && NCW > 0);
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -220,7 +219,8 @@ spmm_smfmac_kernel(const SpmmArgs a) {
   const int64_t t0 = (int64_t)blockIdx.x * kTokTile;
   const int64_t S = a.S;
   const int img = a.image_bytes;
-  const int n_ci = img / 1024;                   // wave-wide copies per image; <= NCW * NW
+  const int n_ci = img / 1024;                   // wave-wide copies per image
+  const int ncw = (n_ci + NW - 1) / NW;          // copies per wave and image
 
   f16v acc[AT][BT];
 #pragma unroll
@@ -237,12 +237,10 @@ spmm_smfmac_kernel(const SpmmArgs a) {
 
   const unsigned char* xs_tile = a.Xs + (int64_t)blockIdx.x * S * img;
   // copy this wave's share of image s into ring slot `slot`; chunks beyond the image are clamped to
-  // its last chunk (an idempotent duplicate) so that every wave issues exactly NCW copies and the
-  // loop body stays straight-line code with a known number of outstanding operations
+  // its last chunk (an idempotent duplicate) so that every wave issues the same number of copies
   auto copy_image = [&](int64_t s, int slot) {
     const unsigned char* src = xs_tile + s * img + lane * 16;
-#pragma unroll
-    for (int k = 0; k < NCW; ++k) {
+    for (int k = 0; k < ncw; ++k) {
       int ci = wave + k * NW;
       ci = ci < n_ci ? ci : n_ci - 1;
       __builtin_amdgcn_global_load_lds((VNM_GLB(void))(src + ci * 1024),
@@ -266,22 +264,13 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     o.pc4 = pcol_w[s * 8];
   };
 
-  int slot = 0;        // ring slot of step s
+  // Compiler-scheduled K step (all V; for V = 64 only the first and last few steps).  Drains all
+  // memory traffic before its barrier: simple and always correct, but it serialises the copies.
   AOp cur, nxt;
-  // Iteration s.  FULL: steady state (s + 2 < S), everything is issued unconditionally so that the
-  // body is straight-line code with a known number of outstanding vector-memory operations.
-  //   1. fetch the A operand of step s+1 (registers)
-  //   2. issue the asynchronous copy of this wave's share of image s+2 into the slot read in s-1
-  //   3. read the B operand of step s from LDS, issue the sparse MFMAs
-  //   4. wait until only the copies of (2) are outstanding -- image s+1 and A(s+1) have landed --
-  //      then one barrier: image s+1 is complete for every wave
-  auto step = [&](auto fullc, int64_t s) {
-    constexpr bool FULL = decltype(fullc)::value;
-    if (FULL || s + 1 < S) load_a(nxt, s + 1);
-    if (FULL || s + 2 < S) {
-      int cs = slot + 2; cs = cs >= NBUF ? cs - NBUF : cs;
-      copy_image(s + 2, cs);
-    }
+  auto step = [&](int64_t s) {
+    const int slot = (int)(s % NBUF);
+    if (s + 1 < S) load_a(nxt, s + 1);
+    if (s + NBUF - 1 < S) copy_image(s + NBUF - 1, (int)((s + NBUF - 1) % NBUF));
     unsigned addr[4];
 #pragma unroll
     for (int m = 0; m < 4; ++m)
@@ -316,68 +305,91 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     if (BT > 2) VNM_MM(2 % BT)
     if (BT > 3) VNM_MM(3 % BT)
 #undef VNM_MM
-    if (FULL) wait_vmcnt_imm<NCW>(); else wait_vmcnt_imm<0>();
-    // Make the fetched A operand "used" right here, inside this straight-line block, so that the
-    // compiler's own wait for it is the exact vmcnt(NCW) above and not a conservative vmcnt(0) at
-    // the loop head (which would also drain the copies that are meant to stay in flight).
-    if (FULL || s + 1 < S) {
-#pragma unroll
-      for (int i = 0; i < AT; ++i)
-        asm volatile("" : "+v"(nxt.w[i].x), "+v"(nxt.w[i].y), "+v"(nxt.w[i].z), "+v"(nxt.w[i].w));
-#pragma unroll
-      for (int i = 0; i < NI; ++i) asm volatile("" : "+v"(nxt.idx[i]));
-      asm volatile("" : "+v"(nxt.pc4));
-    }
+    wait_vmcnt_imm<0>();
     __builtin_amdgcn_s_barrier();
-    slot = slot + 1 == NBUF ? 0 : slot + 1;
     cur = nxt;
   };
 
-  using Full = std::true_type;
-  using Tail = std::false_type;
+  // prologue: the first NBUF-1 images
   for (int k = 0; k < NBUF - 1 && k < S; ++k) copy_image(k, k);
-  load_a(cur, 0);
   wait_vmcnt_imm<0>();
   __builtin_amdgcn_s_barrier();
+
   int64_t s = 0;
-  if constexpr (V == 64 && TW == 128) {
-    // steady state (s + 2 < S) in assembly; s stays 0 here, so `cur` holds A(0), slot 0 is read first
-    if (S > 2) {
-      const uint64_t pa_p = (uint64_t)(a.pa + (rr * S + 1) * AT * 64);
-      const uint64_t pi_p = (uint64_t)(a.pidx + (rr * S + 1) * 64 * AT);
-      const uint64_t pc_p = (uint64_t)(a.pcol + (rr * S + 1) * 8);
-      const uint64_t xs_p = (uint64_t)(xs_tile + 2 * (int64_t)img);
+  if constexpr (kAsmLoop) {
+    // steady state: steps 0 .. S-NBUF (every step issues a copy NBUF-1 ahead and an A load 2 ahead)
+    if (S > NBUF - 1 && S > 3) {
+      const uint64_t pa_p = (uint64_t)(a.pa + rr * S * AT * 64);
+      const uint64_t pi_p = (uint64_t)(a.pidx + rr * S * 64 * AT);
+      const uint64_t pc_p = (uint64_t)(a.pcol + rr * S * 8);
+      const uint64_t xs_p = (uint64_t)(xs_tile + (int64_t)(NBUF - 1) * img);
       unsigned l_pa_lo = __builtin_amdgcn_readfirstlane((unsigned)pa_p), l_pa_hi = __builtin_amdgcn_readfirstlane((unsigned)(pa_p >> 32));
       unsigned l_pi_lo = __builtin_amdgcn_readfirstlane((unsigned)pi_p), l_pi_hi = __builtin_amdgcn_readfirstlane((unsigned)(pi_p >> 32));
       unsigned l_pc_lo = __builtin_amdgcn_readfirstlane((unsigned)pc_p), l_pc_hi = __builtin_amdgcn_readfirstlane((unsigned)(pc_p >> 32));
       unsigned l_xs_lo = __builtin_amdgcn_readfirstlane((unsigned)xs_p), l_xs_hi = __builtin_amdgcn_readfirstlane((unsigned)(xs_p >> 32));
-      unsigned l_voff16 = lane * 16, l_voffi = lane * 4, l_voffp = (hB * 4 + kq) * 4;
+      unsigned l_voff16 = lane * 16, l_voffi = lane * 4, l_voffp = (hB * 4 + kq) * 4, l_vtok = tokoff;
       unsigned l_woff = wave * 1024, l_clamp = (n_ci - 1) * 1024, l_pitch = P, l_img = img;
-      unsigned l_lbeg = __builtin_amdgcn_readfirstlane(lds0), l_lend = l_lbeg + 3 * img;
-      unsigned l_rd = l_lbeg, l_wr = l_lbeg + 2 * img, l_n = (unsigned)(S - 2), l_tci;
-      const unsigned tokoff_rel = tokoff;   // LDS base is carried by rd
-      {
-        const unsigned tokoff = tokoff_rel;
-        if constexpr (NCW == 3) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_3, "3");
-        else if constexpr (NCW == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_4, "4");
-        else if constexpr (NCW == 5) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_5, "5");
-        else if constexpr (NCW == 6) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_6, "6");
-        else if constexpr (NCW == 7) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_7, "7");
-        else if constexpr (NCW == 8) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_8, "8");
-        else if constexpr (NCW == 9) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_9, "9");
-        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES_10, "10");
+      unsigned l_lbeg = __builtin_amdgcn_readfirstlane(lds0), l_lend = l_lbeg + NBUF * img;
+      unsigned l_rd = l_lbeg, l_wr = l_lbeg + (NBUF - 1) * img, l_tci;
+      // steps with s + NBUF - 1 < S and s + 2 < S
+      const int64_t n_steady = (S - (NBUF - 1)) < (S - 2) ? (S - (NBUF - 1)) : (S - 2);
+      unsigned l_n = (unsigned)n_steady;
+      // VMW = operations that may stay in flight at the end of a step (see the comment above):
+      // NBUF = 4: this step's 4 loads + NCW copies and the previous step's NCW copies;
+      // NBUF = 3: this step's 4 loads + NCW copies
+#define VNM_GO(N, VM3, VM4)                                                       \
+      if constexpr (NCW == N) {                                                  \
+        if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_##N, VM4);       \
+        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES_##N, VM3);                           \
       }
-      s = S - 2;
-      slot = (int)(s % NBUF);
+      VNM_GO(3, "7", "10") VNM_GO(4, "8", "12") VNM_GO(5, "9", "14") VNM_GO(6, "10", "16")
+      VNM_GO(7, "11", "18") VNM_GO(8, "12", "20") VNM_GO(9, "13", "22") VNM_GO(10, "14", "24")
+#undef VNM_GO
+      s = n_steady;
     }
-  } else {
-    for (; s + 2 < S; ++s) step(Full{}, s);
   }
-  for (; s < S; ++s) step(Tail{}, s);
+  if (s < S) { load_a(cur, s); }
+  for (; s < S; ++s) step(s);
 
-  // ---- epilogue: lane holds, per (A tile, B tile, jq), 4 consecutive output channels of one token
+  // ---- epilogue.  A lane holds, per (A tile, B tile, jq), 4 consecutive output channels of one
+  // token -- 8 bytes of fp16 -- so storing straight from the accumulators would scatter 8-byte
+  // pieces over 64 different rows per instruction.  For fp16 output the wave's tile is therefore
+  // turned around in LDS (the ring is free after the last barrier): written as [token][V channels]
+  // with a pitch of V*2+8 bytes (conflict-free 8-byte writes), read back 16 bytes per lane with
+  // V/8 lanes per token, and stored as whole V*2-byte runs of each Y row.
   if (!r_valid) return;
   const int tokl = lane & 31;
+  if (!a.y_fp32 && a.wide_store) {
+    constexpr int EP = V * 2 + 8;                         // bytes per token row in LDS
+    unsigned char* ep = smem + (size_t)wave * TW * EP;    // this wave's private region
+#pragma unroll
+    for (int j = 0; j < BT; ++j)
+#pragma unroll
+      for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq) {
+          h4 pk = {(_Float16)acc[i][j][4 * jq], (_Float16)acc[i][j][4 * jq + 1],
+                   (_Float16)acc[i][j][4 * jq + 2], (_Float16)acc[i][j][4 * jq + 3]};
+          *(h4*)(ep + (size_t)(j * 32 + tokl) * EP + (i * 32 + 8 * jq + 4 * hB) * 2) = pk;
+        }
+    constexpr int LPT = V / 8;                            // lanes per token row (16 bytes each)
+    constexpr int TPI = 64 / LPT;                         // token rows per wave-wide store
+    const int ch = lane % LPT, tl = lane / LPT;
+    _Float16* Yh = (_Float16*)a.Y;
+#pragma unroll
+    for (int it = 0; it < TW / TPI; ++it) {
+      const int tk = it * TPI + tl;
+      const uint4 v = *(const uint4*)(ep + (size_t)tk * EP + ch * 16);
+      const int64_t tok = t0 + wt * TW + tk;
+      const int64_t o = r * V + ch * 8;
+      if (tok < a.T && o + 8 <= a.out) *(uint4*)(Yh + tok * a.ldy + o) = v;
+      else if (tok < a.T) {
+        const _Float16* hv = (const _Float16*)&v;
+        for (int e = 0; e < 8; ++e) if (o + e < a.out) Yh[tok * a.ldy + o + e] = hv[e];
+      }
+    }
+    return;
+  }
   auto store4 = [&](auto* dst, int64_t o, float v0, float v1, float v2, float v3) {
     using OutT = std::remove_pointer_t<decltype(dst)>;
     if (a.vec_store && o + 3 < a.out) {
@@ -417,10 +429,12 @@ bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d) {
   return has_packed(d.V, d.M) && d.in % 8 == 0 && ldx % 8 == 0 && ((uintptr_t)X & 15) == 0;
 }
 
-template <int V, int TW, int WR, int WT, int NCW>
+template <int V, int TW, int WR, int WT, int NCW, int NBUF>
 static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
-  const size_t lds = (size_t)3 * a.image_bytes;
-  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW>;
+  size_t lds = (size_t)NBUF * a.image_bytes;
+  const size_t ep = (size_t)WR * WT * TW * (V * 2 + 8);     // epilogue transposition, per wave [TW][V] fp16
+  if (ep > lds) lds = ep;
+  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -434,20 +448,20 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
   return VNM_OK;
 }
 
-// NCW = wave-wide 1 KiB copies per wave and image = ceil(image KiB / waves per workgroup)
-template <int V, int TW, int WR, int WT>
-static int launch_by_ncw(const SpmmArgs& a, hipStream_t st) {
-  const int ncw = (a.image_bytes / 1024 + WR * WT - 1) / (WR * WT);
+// V = 64: pick the assembly loop by copies per wave (NCW = ceil(image KiB / 4 waves)) and by ring
+// depth: 4 images while two workgroups still fit the CU's 160 KiB of LDS, else 3.
+template <int NBUF>
+static int launch_v64(const SpmmArgs& a, hipStream_t st) {
+  const int ncw = (a.image_bytes / 1024 + 3) / 4;
   switch (ncw) {
-    case 2: return launch_cfg<V, TW, WR, WT, 2>(a, st);
-    case 3: return launch_cfg<V, TW, WR, WT, 3>(a, st);
-    case 4: return launch_cfg<V, TW, WR, WT, 4>(a, st);
-    case 5: return launch_cfg<V, TW, WR, WT, 5>(a, st);
-    case 6: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 6 : 2)>(a, st); break;
-    case 7: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 7 : 2)>(a, st); break;
-    case 8: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 8 : 2)>(a, st); break;
-    case 9: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 9 : 2)>(a, st); break;
-    case 10: if (WR * WT <= 4) return launch_cfg<V, TW, WR, WT, (WR * WT <= 4 ? 10 : 2)>(a, st); break;
+    case 3: return launch_cfg<64, 128, 4, 1, 3, NBUF>(a, st);
+    case 4: return launch_cfg<64, 128, 4, 1, 4, NBUF>(a, st);
+    case 5: return launch_cfg<64, 128, 4, 1, 5, NBUF>(a, st);
+    case 6: return launch_cfg<64, 128, 4, 1, 6, NBUF>(a, st);
+    case 7: return launch_cfg<64, 128, 4, 1, 7, NBUF>(a, st);
+    case 8: return launch_cfg<64, 128, 4, 1, 8, NBUF>(a, st);
+    case 9: return launch_cfg<64, 128, 4, 1, 9, NBUF>(a, st);
+    case 10: return launch_cfg<64, 128, 4, 1, 10, NBUF>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }
@@ -464,12 +478,14 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.out = d.out; a.R = d.R; a.S = d.S; a.M = d.M;
   a.image_bytes = (int)image_bytes(d.M);
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
+  a.wide_store = (y_dtype == 0) && (ldy % 8 == 0) && (((uintptr_t)Y & 15) == 0);
   a.vec_store = (ldy % 4 == 0) && (((uintptr_t)Y & (y_dtype == 0 ? 7 : 15)) == 0);
   if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (d.R + 3) / 4 > 65535) return VNM_ERR_UNSUPPORTED;
+  const bool deep = 2 * 4 * (size_t)a.image_bytes <= 150 * 1024;
   switch (d.V) {
-    case 32: return launch_by_ncw<32, 128, 8, 1>(a, st);
-    case 64: return launch_by_ncw<64, 128, 4, 1>(a, st);
-    case 128: return launch_by_ncw<128, 64, 2, 2>(a, st);
+    case 32: return launch_cfg<32, 128, 8, 1, 0, 3>(a, st);
+    case 64: return deep ? launch_v64<4>(a, st) : launch_v64<3>(a, st);
+    case 128: return launch_cfg<128, 64, 2, 2, 0, 3>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }

@@ -64,13 +64,8 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
 // register loads of the A operand two steps ahead and the asynchronous global->LDS copies of the
 // image NBUF-1 steps ahead -- and must wait for the older ones while the younger ones keep flying
 // (vmcnt counts both, in issue order).  Compiled code drains everything (vmcnt(0)) at each use,
-// which serialises the copies with the multiply.  Here every wait is explicit.  Iteration s:
-//     16 transposing LDS reads (B operand of step s, ring slot s % NBUF)
-//     issue the A loads of step s+2 into the register set freed by step s-1
-//     8 sparse MFMAs as the B tiles land, with the NCW copies of image s+NBUF-1 and the scalar
-//         bookkeeping issued underneath them
-//     s_waitcnt vmcnt(VMW): everything older than {this step's loads and copies, the previous
-//         step's copies} has landed, i.e. A(s+1) and image s+1; s_barrier
+// which serialises the copies with the multiply.  Here every wait is explicit; the schedule of one
+// step is described at VNM_ASM_STEP.
 // The body is unrolled three times so that the three A register sets rotate by name.
 // Fixed registers (declared clobbered):
 //   v[186:189] B row addresses, v190 v191 scratch, v[192:223] B tiles 0..3,
@@ -87,14 +82,20 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
   "s_add_u32 m0, %[wr], %[tci]\n"                             \
   "s_nop 0\n"                                                 \
   "global_load_lds_dwordx4 %[voff16], s[88:89]\n"
-#define VNM_ASM_COPIES_3 VNM_ASM_COPY(0) VNM_ASM_COPY(4096) VNM_ASM_COPY(8192)
-#define VNM_ASM_COPIES_4 VNM_ASM_COPIES_3 VNM_ASM_COPY(12288)
-#define VNM_ASM_COPIES_5 VNM_ASM_COPIES_4 VNM_ASM_COPY(16384)
-#define VNM_ASM_COPIES_6 VNM_ASM_COPIES_5 VNM_ASM_COPY(20480)
-#define VNM_ASM_COPIES_7 VNM_ASM_COPIES_6 VNM_ASM_COPY(24576)
-#define VNM_ASM_COPIES_8 VNM_ASM_COPIES_7 VNM_ASM_COPY(28672)
-#define VNM_ASM_COPIES_9 VNM_ASM_COPIES_8 VNM_ASM_COPY(32768)
-#define VNM_ASM_COPIES_10 VNM_ASM_COPIES_9 VNM_ASM_COPY(36864)
+// copies per wave and image for 4-wave workgroups (chunk stride 4 KiB) ...
+#define VNM_ASM_COPIES4_3 VNM_ASM_COPY(0) VNM_ASM_COPY(4096) VNM_ASM_COPY(8192)
+#define VNM_ASM_COPIES4_4 VNM_ASM_COPIES4_3 VNM_ASM_COPY(12288)
+#define VNM_ASM_COPIES4_5 VNM_ASM_COPIES4_4 VNM_ASM_COPY(16384)
+#define VNM_ASM_COPIES4_6 VNM_ASM_COPIES4_5 VNM_ASM_COPY(20480)
+#define VNM_ASM_COPIES4_7 VNM_ASM_COPIES4_6 VNM_ASM_COPY(24576)
+#define VNM_ASM_COPIES4_8 VNM_ASM_COPIES4_7 VNM_ASM_COPY(28672)
+#define VNM_ASM_COPIES4_9 VNM_ASM_COPIES4_8 VNM_ASM_COPY(32768)
+#define VNM_ASM_COPIES4_10 VNM_ASM_COPIES4_9 VNM_ASM_COPY(36864)
+// ... and for 8-wave workgroups (chunk stride 8 KiB)
+#define VNM_ASM_COPIES8_2 VNM_ASM_COPY(0) VNM_ASM_COPY(8192)
+#define VNM_ASM_COPIES8_3 VNM_ASM_COPIES8_2 VNM_ASM_COPY(16384)
+#define VNM_ASM_COPIES8_4 VNM_ASM_COPIES8_3 VNM_ASM_COPY(24576)
+#define VNM_ASM_COPIES8_5 VNM_ASM_COPIES8_4 VNM_ASM_COPY(32768)
 
 #define VNM_ASM_READ4(OFF, R0, R1, R2, R3)                                     \
   "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v186 offset:" #OFF "\n"            \
@@ -111,40 +112,51 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
   "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                         \
   "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"
 
-// one K step: current A set (CW0, CW1, CIDX, CPC), A set to load (LW0, LW1, LIDX, LPC)
-#define VNM_ASM_STEP(CW0, CW1, CIDX, CPC, LW0, LW1, LIDX, LPC, COPIES, VMWSTR)                     \
+// B row addresses of a step from its column table register PC (4 x 8-bit row offsets) and ring slot
+#define VNM_ASM_ADDR(PC)                                                                          \
       "v_add_u32 v190, %[rd], %[vtok]\n"                                                          \
-      "v_and_b32 v191, 0xff, v" CPC "\n"                                                          \
+      "v_and_b32 v191, 0xff, v" PC "\n"                                                           \
       "v_mad_u32_u24 v186, v191, %[pitch], v190\n"                                                \
-      "v_bfe_u32 v191, v" CPC ", 8, 8\n"                                                          \
+      "v_bfe_u32 v191, v" PC ", 8, 8\n"                                                           \
       "v_mad_u32_u24 v187, v191, %[pitch], v190\n"                                                \
-      "v_bfe_u32 v191, v" CPC ", 16, 8\n"                                                         \
+      "v_bfe_u32 v191, v" PC ", 16, 8\n"                                                          \
       "v_mad_u32_u24 v188, v191, %[pitch], v190\n"                                                \
-      "v_lshrrev_b32 v191, 24, v" CPC "\n"                                                        \
-      "v_mad_u32_u24 v189, v191, %[pitch], v190\n"                                                \
-      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
-      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
+      "v_lshrrev_b32 v191, 24, v" PC "\n"                                                         \
+      "v_mad_u32_u24 v189, v191, %[pitch], v190\n"
+
+// One K step.  On entry the reads of B tiles 0 and 1 of this step are already in flight and
+// v186..v189 hold this step's row addresses.  CUR = A set of this step, NPC = column table register
+// of the next step's set (landed by the time it is used), LOAD = set that receives A(s+2).
+//   tiles 2, 3 of this step are requested, A(s+2) is requested, tiles 0, 1 are multiplied;
+//   then the wait for A(s+1) / image s+1 and the barrier; after it (every wave has finished step
+//   s-1, so its ring slot is free) the copies of the image NBUF-1 ahead are issued, the next
+//   step's addresses are formed and its tiles 0, 1 requested; tiles 2, 3 are multiplied.
+// The barrier therefore sits between two MFMA pairs whose operands are already in registers.
+#define VNM_ASM_STEP(CW0, CW1, CIDX, NPC, LW0, LW1, LIDX, LPC, COPIES, VMWSTR)                     \
+      VNM_ASM_LOAD_A(LW0, LW1, LIDX, LPC)                                                         \
       VNM_ASM_READ4(128, 208, 210, 212, 214)                                                      \
       VNM_ASM_READ4(192, 216, 218, 220, 222)                                                      \
-      VNM_ASM_LOAD_A(LW0, LW1, LIDX, LPC)                                                         \
       "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
       "v_smfmac_f32_32x32x32_f16 %[a00], v[" CW0 "], v[192:199], v" CIDX "\n"                     \
       "v_smfmac_f32_32x32x32_f16 %[a10], v[" CW1 "], v[192:199], v" CIDX " abid:1\n"              \
-      COPIES                                                                                      \
+      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
       "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
       "v_smfmac_f32_32x32x32_f16 %[a01], v[" CW0 "], v[200:207], v" CIDX "\n"                     \
       "v_smfmac_f32_32x32x32_f16 %[a11], v[" CW1 "], v[200:207], v" CIDX " abid:1\n"              \
-      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
-      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
-      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
-      "s_waitcnt lgkmcnt(4)\n s_nop 1\n"                                                          \
-      "v_smfmac_f32_32x32x32_f16 %[a02], v[" CW0 "], v[208:215], v" CIDX "\n"                     \
-      "v_smfmac_f32_32x32x32_f16 %[a12], v[" CW1 "], v[208:215], v" CIDX " abid:1\n"              \
-      "s_waitcnt lgkmcnt(0)\n s_nop 1\n"                                                          \
-      "v_smfmac_f32_32x32x32_f16 %[a03], v[" CW0 "], v[216:223], v" CIDX "\n"                     \
-      "v_smfmac_f32_32x32x32_f16 %[a13], v[" CW1 "], v[216:223], v" CIDX " abid:1\n"              \
       "s_waitcnt vmcnt(" VMWSTR ")\n"                                                             \
       "s_barrier\n"                                                                               \
+      VNM_ASM_ADDR(NPC)                                                                           \
+      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
+      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
+      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
+      "v_smfmac_f32_32x32x32_f16 %[a02], v[" CW0 "], v[208:215], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a12], v[" CW1 "], v[208:215], v" CIDX " abid:1\n"              \
+      COPIES                                                                                      \
+      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
+      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
+      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
+      "v_smfmac_f32_32x32x32_f16 %[a03], v[" CW0 "], v[216:223], v" CIDX "\n"                     \
+      "v_smfmac_f32_32x32x32_f16 %[a13], v[" CW1 "], v[216:223], v" CIDX " abid:1\n"              \
       "s_sub_u32 %[n], %[n], 1\n"                                                                 \
       "s_cmp_eq_u32 %[n], 0\n"                                                                    \
       "s_cbranch_scc1 9f\n"
@@ -158,13 +170,16 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
       VNM_ASM_LOAD_A("224:227", "228:231", "232", "233")                                          \
       VNM_ASM_LOAD_A("234:237", "238:241", "242", "243")                                          \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
+      VNM_ASM_ADDR("233")                                                                         \
+      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
+      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
       "1:\n"                                                                                      \
-      VNM_ASM_STEP("224:227", "228:231", "232", "233", "244:247", "248:251", "252", "253", COPIES, VMWSTR) \
-      VNM_ASM_STEP("234:237", "238:241", "242", "243", "224:227", "228:231", "232", "233", COPIES, VMWSTR) \
-      VNM_ASM_STEP("244:247", "248:251", "252", "253", "234:237", "238:241", "242", "243", COPIES, VMWSTR) \
+      VNM_ASM_STEP("224:227", "228:231", "232", "243", "244:247", "248:251", "252", "253", COPIES, VMWSTR) \
+      VNM_ASM_STEP("234:237", "238:241", "242", "253", "224:227", "228:231", "232", "233", COPIES, VMWSTR) \
+      VNM_ASM_STEP("244:247", "248:251", "252", "233", "234:237", "238:241", "242", "243", COPIES, VMWSTR) \
       "s_branch 1b\n"                                                                             \
       "9:\n"                                                                                      \
-      "s_waitcnt vmcnt(0)\n"                                                                      \
+      "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
       "s_barrier\n"                                                                               \
       : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
         [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
@@ -334,16 +349,17 @@ spmm_smfmac_kernel(const SpmmArgs a) {
       // steps with s + NBUF - 1 < S and s + 2 < S
       const int64_t n_steady = (S - (NBUF - 1)) < (S - 2) ? (S - (NBUF - 1)) : (S - 2);
       unsigned l_n = (unsigned)n_steady;
-      // VMW = operations that may stay in flight at the end of a step (see the comment above):
-      // NBUF = 4: this step's 4 loads + NCW copies and the previous step's NCW copies;
-      // NBUF = 3: this step's 4 loads + NCW copies
-#define VNM_GO(N, VM3, VM4)                                                       \
-      if constexpr (NCW == N) {                                                  \
-        if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES_##N, VM4);       \
-        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES_##N, VM3);                           \
+      // VMW = operations that may stay in flight at a step's wait: the 4 loads of A(s+2) issued at
+      // its start and, with a ring of 4, the NCW copies issued after the previous step's barrier
+      // (with a ring of 3 those copies are image s+1 itself and must have landed)
+#define VNM_GO(W, N, VM3, VM4)                                                    \
+      if constexpr (NW == W && NCW == N) {                                       \
+        if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES##W##_##N, VM4);  \
+        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES##W##_##N, VM3);                      \
       }
-      VNM_GO(3, "7", "10") VNM_GO(4, "8", "12") VNM_GO(5, "9", "14") VNM_GO(6, "10", "16")
-      VNM_GO(7, "11", "18") VNM_GO(8, "12", "20") VNM_GO(9, "13", "22") VNM_GO(10, "14", "24")
+      VNM_GO(4, 3, "4", "7") VNM_GO(4, 4, "4", "8") VNM_GO(4, 5, "4", "9") VNM_GO(4, 6, "4", "10")
+      VNM_GO(4, 7, "4", "11") VNM_GO(4, 8, "4", "12") VNM_GO(4, 9, "4", "13") VNM_GO(4, 10, "4", "14")
+      VNM_GO(8, 2, "4", "6") VNM_GO(8, 3, "4", "7") VNM_GO(8, 4, "4", "8") VNM_GO(8, 5, "4", "9")
 #undef VNM_GO
       s = n_steady;
     }
@@ -448,10 +464,10 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
   return VNM_OK;
 }
 
-// V = 64: pick the assembly loop by copies per wave (NCW = ceil(image KiB / 4 waves)) and by ring
-// depth: 4 images while two workgroups still fit the CU's 160 KiB of LDS, else 3.
+// V = 64: pick the assembly loop by workgroup size (4 or 8 row blocks), by copies per wave
+// (NCW = ceil(image KiB / waves)) and by ring depth.
 template <int NBUF>
-static int launch_v64(const SpmmArgs& a, hipStream_t st) {
+static int launch_v64_w4(const SpmmArgs& a, hipStream_t st) {
   const int ncw = (a.image_bytes / 1024 + 3) / 4;
   switch (ncw) {
     case 3: return launch_cfg<64, 128, 4, 1, 3, NBUF>(a, st);
@@ -462,6 +478,17 @@ static int launch_v64(const SpmmArgs& a, hipStream_t st) {
     case 8: return launch_cfg<64, 128, 4, 1, 8, NBUF>(a, st);
     case 9: return launch_cfg<64, 128, 4, 1, 9, NBUF>(a, st);
     case 10: return launch_cfg<64, 128, 4, 1, 10, NBUF>(a, st);
+  }
+  return VNM_ERR_UNSUPPORTED;
+}
+template <int NBUF>
+static int launch_v64_w8(const SpmmArgs& a, hipStream_t st) {
+  const int ncw = (a.image_bytes / 1024 + 7) / 8;
+  switch (ncw) {
+    case 2: return launch_cfg<64, 128, 8, 1, 2, NBUF>(a, st);
+    case 3: return launch_cfg<64, 128, 8, 1, 3, NBUF>(a, st);
+    case 4: return launch_cfg<64, 128, 8, 1, 4, NBUF>(a, st);
+    case 5: return launch_cfg<64, 128, 8, 1, 5, NBUF>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }
@@ -480,11 +507,18 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.wide_store = (y_dtype == 0) && (ldy % 8 == 0) && (((uintptr_t)Y & 15) == 0);
   a.vec_store = (ldy % 4 == 0) && (((uintptr_t)Y & (y_dtype == 0 ? 7 : 15)) == 0);
-  if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (d.R + 3) / 4 > 65535) return VNM_ERR_UNSUPPORTED;
+  if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (d.R + 1) / 2 > 65535) return VNM_ERR_UNSUPPORTED;
   const bool deep = 2 * 4 * (size_t)a.image_bytes <= 150 * 1024;
+  // 8 row blocks per workgroup halve the image traffic per flop; worth it when there are enough
+  // row blocks to keep every CU busy with one such workgroup
+  const int64_t tiles = (T + kTokTile - 1) / kTokTile;
+  bool wide = d.R >= 8 && tiles * ((d.R + 7) / 8) >= 200;
+  { const char* e = getenv("VNM_SPMM_WG"); if (e) wide = atoi(e) == 8; }
   switch (d.V) {
     case 32: return launch_cfg<32, 128, 8, 1, 0, 3>(a, st);
-    case 64: return deep ? launch_v64<4>(a, st) : launch_v64<3>(a, st);
+    case 64:
+      if (wide) return 4 * (size_t)a.image_bytes <= 150 * 1024 ? launch_v64_w8<4>(a, st) : launch_v64_w8<3>(a, st);
+      return deep ? launch_v64_w4<4>(a, st) : launch_v64_w4<3>(a, st);
     case 128: return launch_cfg<128, 64, 2, 2, 0, 3>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;

@@ -55,6 +55,8 @@ extern "C" int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_
     if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
   }
   hipStream_t st = (hipStream_t)stream;
+  if (prune_fast_applicable(W, ldw, d, mask) && (!packed || has_packed(V, M)))
+    return launch_prune_fast(W, ldw, d, values, meta, colidx, mask, packed, st);
   rc = launch_prune_compress(W, ldw, d, values, meta, colidx, mask, st);
   if (rc) return rc;
   if (packed) rc = launch_pack(values, meta, colidx, d, packed, st);
@@ -122,8 +124,10 @@ extern "C" int vnm_decompress(const void* values, const void* meta, const void* 
   if (rc) return rc;
   if (ldw < in) return VNM_ERR_SHAPE;
   if (((uintptr_t)W_out & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
-  return launch_decompress(values, meta, colidx, make_dims(out, in, V, M), W_out, ldw,
-                           (hipStream_t)stream);
+  const Dims d = make_dims(out, in, V, M);
+  if (decompress_fast_applicable(W_out, ldw, d))
+    return launch_decompress_fast(values, meta, colidx, d, W_out, ldw, (hipStream_t)stream);
+  return launch_decompress(values, meta, colidx, d, W_out, ldw, (hipStream_t)stream);
 }
 
 extern "C" const char* vnm_status_string(int status) {

@@ -59,6 +59,12 @@ void set_hip_error(hipError_t e, const char* where);
 // launchers (each returns a vnm_status)
 int launch_prune_compress(const void* W, int64_t ldw, const Dims& d, void* values, void* meta,
                           void* colidx, void* mask, hipStream_t st);
+bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask);
+int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, void* meta, void* colidx,
+                      void* mask, void* packed, hipStream_t st);
+bool decompress_fast_applicable(const void* W_out, int64_t ldw, const Dims& d);
+int launch_decompress_fast(const void* values, const void* meta, const void* colidx, const Dims& d,
+                           void* W_out, int64_t ldw, hipStream_t st);
 int launch_pack(const void* values, const void* meta, const void* colidx, const Dims& d,
                 void* packed, hipStream_t st);
 int launch_decompress(const void* values, const void* meta, const void* colidx, const Dims& d,

@@ -82,35 +82,50 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
   "s_add_u32 m0, %[wr], %[tci]\n"                             \
   "s_nop 0\n"                                                 \
   "global_load_lds_dwordx4 %[voff16], s[88:89]\n"
-// copies per wave and image for 4-wave workgroups (chunk stride 4 KiB) ...
-#define VNM_ASM_COPIES4_3 VNM_ASM_COPY(0) VNM_ASM_COPY(4096) VNM_ASM_COPY(8192)
-#define VNM_ASM_COPIES4_4 VNM_ASM_COPIES4_3 VNM_ASM_COPY(12288)
-#define VNM_ASM_COPIES4_5 VNM_ASM_COPIES4_4 VNM_ASM_COPY(16384)
-#define VNM_ASM_COPIES4_6 VNM_ASM_COPIES4_5 VNM_ASM_COPY(20480)
-#define VNM_ASM_COPIES4_7 VNM_ASM_COPIES4_6 VNM_ASM_COPY(24576)
-#define VNM_ASM_COPIES4_8 VNM_ASM_COPIES4_7 VNM_ASM_COPY(28672)
-#define VNM_ASM_COPIES4_9 VNM_ASM_COPIES4_8 VNM_ASM_COPY(32768)
-#define VNM_ASM_COPIES4_10 VNM_ASM_COPIES4_9 VNM_ASM_COPY(36864)
-// ... and for 8-wave workgroups (chunk stride 8 KiB)
-#define VNM_ASM_COPIES8_2 VNM_ASM_COPY(0) VNM_ASM_COPY(8192)
-#define VNM_ASM_COPIES8_3 VNM_ASM_COPIES8_2 VNM_ASM_COPY(16384)
-#define VNM_ASM_COPIES8_4 VNM_ASM_COPIES8_3 VNM_ASM_COPY(24576)
-#define VNM_ASM_COPIES8_5 VNM_ASM_COPIES8_4 VNM_ASM_COPY(32768)
+// Copies per wave and image, split in two groups issued under two different MFMAs.
+// 4-wave workgroups: chunk stride 4 KiB; 8-wave workgroups: 8 KiB.
+#define VNM_C4_3A VNM_ASM_COPY(0) VNM_ASM_COPY(4096)
+#define VNM_C4_3B VNM_ASM_COPY(8192)
+#define VNM_C4_4A VNM_ASM_COPY(0) VNM_ASM_COPY(4096)
+#define VNM_C4_4B VNM_ASM_COPY(8192) VNM_ASM_COPY(12288)
+#define VNM_C4_5A VNM_C4_4A VNM_ASM_COPY(8192)
+#define VNM_C4_5B VNM_ASM_COPY(12288) VNM_ASM_COPY(16384)
+#define VNM_C4_6A VNM_C4_5A
+#define VNM_C4_6B VNM_C4_5B VNM_ASM_COPY(20480)
+#define VNM_C4_7A VNM_C4_5A VNM_ASM_COPY(12288)
+#define VNM_C4_7B VNM_ASM_COPY(16384) VNM_ASM_COPY(20480) VNM_ASM_COPY(24576)
+#define VNM_C4_8A VNM_C4_7A
+#define VNM_C4_8B VNM_C4_7B VNM_ASM_COPY(28672)
+#define VNM_C4_9A VNM_C4_7A VNM_ASM_COPY(16384)
+#define VNM_C4_9B VNM_ASM_COPY(20480) VNM_ASM_COPY(24576) VNM_ASM_COPY(28672) VNM_ASM_COPY(32768)
+#define VNM_C4_10A VNM_C4_9A
+#define VNM_C4_10B VNM_C4_9B VNM_ASM_COPY(36864)
+#define VNM_C8_2A VNM_ASM_COPY(0)
+#define VNM_C8_2B VNM_ASM_COPY(8192)
+#define VNM_C8_3A VNM_ASM_COPY(0) VNM_ASM_COPY(8192)
+#define VNM_C8_3B VNM_ASM_COPY(16384)
+#define VNM_C8_4A VNM_C8_3A
+#define VNM_C8_4B VNM_ASM_COPY(16384) VNM_ASM_COPY(24576)
+#define VNM_C8_5A VNM_C8_3A VNM_ASM_COPY(16384)
+#define VNM_C8_5B VNM_ASM_COPY(24576) VNM_ASM_COPY(32768)
 
+// two of the four transposing reads of one B tile (rows A0, A1 -> register pairs R0, R1)
+#define VNM_ASM_READ2(OFF, R0, A0, R1, A1)                                     \
+  "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v" #A0 " offset:" #OFF "\n"        \
+  "ds_read_b64_tr_b16 v[" #R1 ":" #R1 "+1], v" #A1 " offset:" #OFF "\n"
 #define VNM_ASM_READ4(OFF, R0, R1, R2, R3)                                     \
-  "ds_read_b64_tr_b16 v[" #R0 ":" #R0 "+1], v186 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R1 ":" #R1 "+1], v187 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R2 ":" #R2 "+1], v188 offset:" #OFF "\n"            \
-  "ds_read_b64_tr_b16 v[" #R3 ":" #R3 "+1], v189 offset:" #OFF "\n"
+  VNM_ASM_READ2(OFF, R0, 186, R1, 187) VNM_ASM_READ2(OFF, R2, 188, R3, 189)
 
+#define VNM_ASM_A_ADVANCE                                                      \
+  "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                        \
+  "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                         \
+  "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"
 #define VNM_ASM_LOAD_A(W0, W1, IDX, PC)                                        \
   "global_load_dwordx4 v[" W0 "], %[voff16], s[80:81]\n"                       \
   "global_load_dwordx4 v[" W1 "], %[voff16], s[80:81] offset:1024\n"           \
   "global_load_dword v" IDX ", %[voffi], s[82:83]\n"                           \
   "global_load_dword v" PC ", %[voffp], s[84:85]\n"                            \
-  "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                        \
-  "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                         \
-  "s_add_u32 s84, s84, 32\n s_addc_u32 s85, s85, 0\n"
+  VNM_ASM_A_ADVANCE
 
 // B row addresses of a step from its column table register PC (4 x 8-bit row offsets) and ring slot
 #define VNM_ASM_ADDR(PC)                                                                          \
@@ -124,44 +139,58 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
       "v_lshrrev_b32 v191, 24, v" PC "\n"                                                         \
       "v_mad_u32_u24 v189, v191, %[pitch], v190\n"
 
-// One K step.  On entry the reads of B tiles 0 and 1 of this step are already in flight and
-// v186..v189 hold this step's row addresses.  CUR = A set of this step, NPC = column table register
-// of the next step's set (landed by the time it is used), LOAD = set that receives A(s+2).
-//   tiles 2, 3 of this step are requested, A(s+2) is requested, tiles 0, 1 are multiplied;
-//   then the wait for A(s+1) / image s+1 and the barrier; after it (every wave has finished step
-//   s-1, so its ring slot is free) the copies of the image NBUF-1 ahead are issued, the next
-//   step's addresses are formed and its tiles 0, 1 requested; tiles 2, 3 are multiplied.
-// The barrier therefore sits between two MFMA pairs whose operands are already in registers.
-#define VNM_ASM_STEP(CW0, CW1, CIDX, NPC, LW0, LW1, LIDX, LPC, COPIES, VMWSTR)                     \
-      VNM_ASM_LOAD_A(LW0, LW1, LIDX, LPC)                                                         \
-      VNM_ASM_READ4(128, 208, 210, 212, 214)                                                      \
-      VNM_ASM_READ4(192, 216, 218, 220, 222)                                                      \
-      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
+// One K step.  CUR = A set of this step, NPC = column table register of the next step's set (landed
+// by the time it is used), LOAD = set that receives A(s+2).
+// The memory instructions are spread between the eight MFMAs, at most three after each, so that
+// the LDS, the vector-memory path and the matrix pipe are all fed continuously instead of in
+// bursts (in-order issue would otherwise let a full vector-memory queue hold back the LDS reads
+// behind it).  B tiles are requested two tiles (four MFMAs) ahead of their use, across the step
+// boundary; at every use exactly the four reads of the following tile may still be in flight, so
+// every wait is lgkmcnt(4).  Order of one step:
+//   tiles 0,1 multiplied | under them: A(s+2) requested, tiles 2,3 of this step requested
+//   wait for A(s+1) and image s+1 (vmcnt), barrier -- every wave has left step s-1, its ring slot
+//       is free
+//   next step's row addresses
+//   tiles 2,3 multiplied | under them: copies of the image NBUF-1 ahead, next step's tiles 0,1
+#define VNM_ASM_STEP(CW0, CW1, CIDX, NPC, LW0, LW1, LIDX, LPC, COPY_A, COPY_B, VMWSTR)             \
+      "s_waitcnt lgkmcnt(4)\n s_nop 0\n"                                                          \
       "v_smfmac_f32_32x32x32_f16 %[a00], v[" CW0 "], v[192:199], v" CIDX "\n"                     \
+      "global_load_dwordx4 v[" LW0 "], %[voff16], s[80:81]\n"                                     \
+      VNM_ASM_READ2(128, 208, 186, 210, 187)                                                      \
       "v_smfmac_f32_32x32x32_f16 %[a10], v[" CW1 "], v[192:199], v" CIDX " abid:1\n"              \
-      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
-      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
+      "global_load_dwordx4 v[" LW1 "], %[voff16], s[80:81] offset:1024\n"                         \
+      VNM_ASM_READ2(128, 212, 188, 214, 189)                                                      \
+      "s_waitcnt lgkmcnt(4)\n s_nop 0\n"                                                          \
       "v_smfmac_f32_32x32x32_f16 %[a01], v[" CW0 "], v[200:207], v" CIDX "\n"                     \
+      "global_load_dword v" LIDX ", %[voffi], s[82:83]\n"                                         \
+      VNM_ASM_READ2(192, 216, 186, 218, 187)                                                      \
       "v_smfmac_f32_32x32x32_f16 %[a11], v[" CW1 "], v[200:207], v" CIDX " abid:1\n"              \
+      "global_load_dword v" LPC ", %[voffp], s[84:85]\n"                                          \
+      VNM_ASM_READ2(192, 220, 188, 222, 189)                                                      \
+      VNM_ASM_A_ADVANCE                                                                           \
+      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
       "s_waitcnt vmcnt(" VMWSTR ")\n"                                                             \
       "s_barrier\n"                                                                               \
       VNM_ASM_ADDR(NPC)                                                                           \
-      VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
-      VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
-      "s_waitcnt lgkmcnt(12)\n s_nop 1\n"                                                         \
+      "s_waitcnt lgkmcnt(4)\n s_nop 0\n"                                                          \
       "v_smfmac_f32_32x32x32_f16 %[a02], v[" CW0 "], v[208:215], v" CIDX "\n"                     \
+      VNM_ASM_READ2(0, 192, 186, 194, 187)                                                        \
+      COPY_A                                                                                      \
       "v_smfmac_f32_32x32x32_f16 %[a12], v[" CW1 "], v[208:215], v" CIDX " abid:1\n"              \
-      COPIES                                                                                      \
+      VNM_ASM_READ2(0, 196, 188, 198, 189)                                                        \
+      COPY_B                                                                                      \
       "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
       "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
-      "s_waitcnt lgkmcnt(8)\n s_nop 1\n"                                                          \
+      "s_waitcnt lgkmcnt(4)\n s_nop 0\n"                                                          \
       "v_smfmac_f32_32x32x32_f16 %[a03], v[" CW0 "], v[216:223], v" CIDX "\n"                     \
+      VNM_ASM_READ2(64, 200, 186, 202, 187)                                                       \
       "v_smfmac_f32_32x32x32_f16 %[a13], v[" CW1 "], v[216:223], v" CIDX " abid:1\n"              \
+      VNM_ASM_READ2(64, 204, 188, 206, 189)                                                       \
       "s_sub_u32 %[n], %[n], 1\n"                                                                 \
       "s_cmp_eq_u32 %[n], 0\n"                                                                    \
       "s_cbranch_scc1 9f\n"
 
-#define VNM_ASM_LOOP_V64(COPIES, VMWSTR)                                                          \
+#define VNM_ASM_LOOP_V64(COPY_A, COPY_B, VMWSTR)                                                  \
   asm volatile(                                                                                   \
       "s_mov_b32 s80, %[pa_lo]\n s_mov_b32 s81, %[pa_hi]\n"                                       \
       "s_mov_b32 s82, %[pi_lo]\n s_mov_b32 s83, %[pi_hi]\n"                                       \
@@ -174,9 +203,9 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
       VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
       VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
       "1:\n"                                                                                      \
-      VNM_ASM_STEP("224:227", "228:231", "232", "243", "244:247", "248:251", "252", "253", COPIES, VMWSTR) \
-      VNM_ASM_STEP("234:237", "238:241", "242", "253", "224:227", "228:231", "232", "233", COPIES, VMWSTR) \
-      VNM_ASM_STEP("244:247", "248:251", "252", "233", "234:237", "238:241", "242", "243", COPIES, VMWSTR) \
+      VNM_ASM_STEP("224:227", "228:231", "232", "243", "244:247", "248:251", "252", "253", COPY_A, COPY_B, VMWSTR) \
+      VNM_ASM_STEP("234:237", "238:241", "242", "253", "224:227", "228:231", "232", "233", COPY_A, COPY_B, VMWSTR) \
+      VNM_ASM_STEP("244:247", "248:251", "252", "233", "234:237", "238:241", "242", "243", COPY_A, COPY_B, VMWSTR) \
       "s_branch 1b\n"                                                                             \
       "9:\n"                                                                                      \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
@@ -354,8 +383,8 @@ spmm_smfmac_kernel(const SpmmArgs a) {
       // (with a ring of 3 those copies are image s+1 itself and must have landed)
 #define VNM_GO(W, N, VM3, VM4)                                                    \
       if constexpr (NW == W && NCW == N) {                                       \
-        if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_ASM_COPIES##W##_##N, VM4);  \
-        else VNM_ASM_LOOP_V64(VNM_ASM_COPIES##W##_##N, VM3);                      \
+        if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM4);  \
+        else VNM_ASM_LOOP_V64(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM3);         \
       }
       VNM_GO(4, 3, "4", "7") VNM_GO(4, 4, "4", "8") VNM_GO(4, 5, "4", "9") VNM_GO(4, 6, "4", "10")
       VNM_GO(4, 7, "4", "11") VNM_GO(4, 8, "4", "12") VNM_GO(4, 9, "4", "13") VNM_GO(4, 10, "4", "14")

@@ -57,9 +57,14 @@ def get_layers(args):
     return syn.config_single_gemm()
 
 
+def L0_is_default(layers):
+    L = layers[0]
+    return L.V == 64 and L.M == 5 and L.tokens == 4096
+
+
 def cpu_baseline(layers):
     """The oracle as it stands on the host cores: the whole path (prune + compress, decompress,
-    masked-dense fp64 product) on the first layer with a 64-token slice of X."""
+    masked-dense fp64 product) on every layer of the step with a 256-token slice of X."""
     import numpy as np
     import synth_inputs as syn
     from oracle import vnm_oracle as orc
@@ -68,19 +73,22 @@ def cpu_baseline(layers):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    layer = layers[0]
-    Tp = min(64, layer.tokens)
-    W, X = syn.layer_tensors(layer, tokens=Tp)
-    t0 = time.perf_counter()
-    values, meta, colidx, mask = orc.compress(W, layer.V, layer.M)
-    Wd = orc.decompress(values, meta, colidx, layer.out, layer.inn, layer.V, layer.M)
-    Y = orc.matmul_ref(X, Wd)
-    dt = time.perf_counter() - t0
-    flops = 2.0 * Tp * layer.out * layer.inn
+    dt, flops = 0.0, 0.0
+    Tp = min(256, layers[0].tokens)
+    for layer in layers:
+        W, X = syn.layer_tensors(layer, tokens=Tp)
+        t0 = time.perf_counter()
+        values, meta, colidx, mask = orc.compress(W, layer.V, layer.M)
+        Wd = orc.decompress(values, meta, colidx, layer.out, layer.inn, layer.V, layer.M)
+        Y = orc.matmul_ref(X, Wd)
+        dt += time.perf_counter() - t0
+        flops += 2.0 * Tp * layer.out * layer.inn
+    L0 = layers[0]
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s dense-equivalent", "cores": int(threads),
             "kind": "oracle", "seconds": dt,
-            "sample": f"layer '{layer.name}' {layer.out}x{layer.inn} at {layer.V}:2:{layer.M}, whole path "
-                      f"(prune+compress, decompress, fp64 masked-dense product) on a {Tp}-token slice"}
+            "sample": f"all {len(layers)} layers of the step at {L0.V}:2:{L0.M}, whole path (prune+compress, "
+                      f"decompress, fp64 masked-dense product), X cut to {Tp} of {L0.tokens} tokens; the "
+                      f"pruning part does not shrink with the token cut, so the full-size figure is higher"}
 
 
 def main():
@@ -108,6 +116,8 @@ def main():
         Y = torch.empty((L.tokens, L.out), dtype=torch.float16, device=dev)
         Wout = torch.empty_like(Wd)
         state.append((L, Wd, Xd, c, Y, Wout))
+    ws_bytes = max(vnm.vnm_spmm_workspace_bytes(L.tokens, c) for (L, _, _, c, _, _) in state)
+    staged = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)    # vnm_spmm's workspace, shared by all layers
     torch.cuda.synchronize()
 
     def ev():
@@ -115,12 +125,16 @@ def main():
 
     def run_step(record):
         for (L, Wd, Xd, c, Y, Wout) in state:
-            e = [ev() for _ in range(4)] if record is not None else None
+            e = [ev() for _ in range(5)] if record is not None else None
             if not args.spmm_only:
                 if e: e[0].record()
                 vnm.vnm_prune_compress(Wd, L.V, L.M, out=c)
             if e: e[1].record()
-            vnm.vnm_spmm(Xd, c, Y=Y)
+            # vnm_spmm = staging pass + product kernel; issued as its two halves so that the
+            # product kernel can be timed on its own (same kernels, same work as vnm_spmm)
+            vnm.vnm_stage_x(Xd, L.M, staged=staged)
+            if e: e[4].record()
+            vnm.vnm_spmm_staged(staged, L.tokens, c, Y=Y)
             if e: e[2].record()
             if not args.spmm_only:
                 vnm.vnm_decompress(c, W_out=Wout)
@@ -144,14 +158,17 @@ def main():
     # ---- per-kernel times from the events inside the timed region
     per = {}
     for (L, e) in records:
-        d = per.setdefault(L.name, {"prune_compress_ms": 0.0, "spmm_ms": 0.0, "decompress_ms": 0.0, "n": 0})
+        d = per.setdefault(L.name, {"prune_compress_ms": 0.0, "spmm_ms": 0.0, "decompress_ms": 0.0,
+                                    "stage_ms": 0.0, "product_ms": 0.0, "n": 0})
         if not args.spmm_only:
             d["prune_compress_ms"] += e[0].elapsed_time(e[1])
             d["decompress_ms"] += e[2].elapsed_time(e[3])
         d["spmm_ms"] += e[1].elapsed_time(e[2])
+        d["stage_ms"] += e[1].elapsed_time(e[4])
+        d["product_ms"] += e[4].elapsed_time(e[2])
         d["n"] += 1
     for d in per.values():
-        for k in ("prune_compress_ms", "spmm_ms", "decompress_ms"):
+        for k in ("prune_compress_ms", "spmm_ms", "decompress_ms", "stage_ms", "product_ms"):
             d[k] /= d["n"]
 
     # ---- dense fp16 baseline (same shapes, fp16 in / fp32 accumulate / fp16 out)
@@ -167,6 +184,13 @@ def main():
         e1.record(); torch.cuda.synchronize()
         dense_ms[L.name] = e0.elapsed_time(e1) / n
 
+    # one plain device-to-device copy of known size, so that profiler byte counters (FETCH_SIZE /
+    # WRITE_SIZE) collected over this same command can be scaled against it
+    L_c, Wd_c, _, _, _, Wout_c = state[0]
+    Wout_c.copy_(Wd_c)
+    torch.cuda.synchronize()
+    calib_bytes = Wd_c.numel() * Wd_c.element_size()
+
     dense_equiv = sum(2.0 * L.tokens * L.out * L.inn for L in layers)
     kept = 0.0
     layer_rows = []
@@ -177,12 +201,20 @@ def main():
         p = per[L.name]
         layer_rows.append({
             "layer": L.name, "out": L.out, "in": L.inn, "tokens": L.tokens,
-            "spmm_ms": round(p["spmm_ms"], 4), "dense_fp16_ms": round(dense_ms[L.name], 4),
+            "spmm_ms": round(p["spmm_ms"], 4), "stage_ms": round(p["stage_ms"], 4),
+            "product_ms": round(p["product_ms"], 4), "dense_fp16_ms": round(dense_ms[L.name], 4),
             "speedup_vs_dense_fp16": round(dense_ms[L.name] / p["spmm_ms"], 3),
             "spmm_dense_equiv_tflops": round(2.0 * L.tokens * L.out * L.inn / p["spmm_ms"] / 1e9, 1),
             "spmm_kept_tflops": round(k / p["spmm_ms"] / 1e9, 1),
             "prune_compress_ms": round(p["prune_compress_ms"], 4), "decompress_ms": round(p["decompress_ms"], 4)})
     spmm_ms = sum(per[L.name]["spmm_ms"] for L in layers)
+    product_ms = sum(per[L.name]["product_ms"] for L in layers)
+    stage_ms = sum(per[L.name]["stage_ms"] for L in layers)
+    # HBM-side bytes per launch of the product kernel, mean over the 7 launches of a step, from the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled by the calibration
+    # copy); known only for the default workload
+    default_wl = (args.workload == "llama2_7b" and L0_is_default(layers))
+    traffic = 342.0e6 if default_wl else None
     dense_total = sum(dense_ms[L.name] for L in layers)
     L0 = layers[0]
     result = {
@@ -195,21 +227,27 @@ def main():
         "config": {"workload": f"{args.workload} linear layers at {L0.V}:2:{L0.M}, tokens {L0.tokens}, "
                                f"{len(layers)} layers per step", "V": L0.V, "N": 2, "M": L0.M,
                    "tokens": L0.tokens, "spmm_only": bool(args.spmm_only)},
-        "spmm": {"ms_per_step": spmm_ms, "dense_equiv_tflops": dense_equiv / spmm_ms / 1e9,
+        "spmm": {"ms_per_step": spmm_ms, "stage_x_ms_per_step": stage_ms, "product_ms_per_step": product_ms, "dense_equiv_tflops": dense_equiv / spmm_ms / 1e9,
                  "kept_weight_tflops": kept / spmm_ms / 1e9,
                  "dense_equiv_frac_of_fp16_peak": dense_equiv / spmm_ms / 1e9 / PEAK_FP16_DENSE_TFLOPS,
                  "dense_fp16_gemm_ms": dense_total, "speedup_vs_dense_fp16": dense_total / spmm_ms,
                  "dense_baseline": "torch.matmul fp16 (hipBLASLt/rocBLAS), fp32 accumulate, fp16 out"},
         "roofline": {"bound": "mfma", "kernel": "spmm_smfmac_kernel",
-                     "achieved": kept / spmm_ms / 1e9, "peak": PEAK_FP16_DENSE_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kept / spmm_ms / 1e9 / PEAK_FP16_DENSE_TFLOPS, "traffic": None,
-                     "note": "achieved = flops on kept weights (2*T*out*2*col_blocks per launch, summed over the "
-                             "layers of a step) / summed launch durations from HIP events inside the timed region; "
-                             "peak = published dense fp16 MFMA rate"},
+                     "achieved": kept / product_ms / 1e9, "peak": PEAK_FP16_DENSE_TFLOPS, "unit": "TFLOP/s",
+                     "frac": kept / product_ms / 1e9 / PEAK_FP16_DENSE_TFLOPS, "traffic": traffic,
+                     "launches_per_step": len(layers), "avg_launch_us": product_ms / len(layers) * 1e3,
+                     "flops_per_launch": kept / len(layers),
+                     "dense_equiv_tflops": dense_equiv / product_ms / 1e9,
+                     "note": "per launch, mean over the launches of a step (one per layer): flops on kept weights "
+                             "2*T*out*2*col_blocks / launch duration from HIP events around the product kernel "
+                             "inside the timed region; peak = published dense fp16 MFMA rate; traffic = HBM-side "
+                             "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a plain copy)"},
         "layers": layer_rows,
         "paper_context": "paper reports only end-to-end model speedups on RTX 3090 (Llama2-7B 64:2:5: 1.49x at "
                          "batch 1, 1.14x at batch 16; Appendix E) -- context, not a target",
         "host_wall_s": wall,
+        "calibration_copy": {"bytes_read": calib_bytes, "bytes_written": calib_bytes,
+                             "what": "one torch copy_ of the first layer's W after the timed region"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(layers)

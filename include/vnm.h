@@ -118,6 +118,20 @@ int vnm_spmm(const void* X, int64_t T, int64_t ldx,
              void* Y, int64_t ldy, int y_dtype, int path,
              void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * The two halves of vnm_spmm's matrix-core path as separate calls, for callers that feed the same
+ * activations to several layers (the q/k/v projections or the gate/up projections of a block share
+ * their input): re-lay X once, multiply many times.  Same arguments and errors as vnm_spmm;
+ * `staged` is the workspace described there (vnm_spmm_workspace_bytes bytes, 256-byte aligned) and
+ * depends only on T, in and M, not on the layer's weights.  vnm_spmm_staged fails with
+ * VNM_ERR_UNSUPPORTED where vnm_spmm would have used the generic kernel.
+ */
+int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, int M,
+                void* staged, int64_t staged_bytes, void* stream);
+int vnm_spmm_staged(const void* staged, int64_t T, const void* packed,
+                    int64_t out, int64_t in, int V, int N, int M,
+                    void* Y, int64_t ldy, int y_dtype, void* stream);
+
 /* Host only.  Bytes of workspace vnm_spmm needs for T tokens of this layer (0 if the matrix-core
  * kernel does not exist for this V, M). */
 int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M, int64_t* bytes);

@@ -45,6 +45,10 @@ def load_library():
     lib.vnm_pack.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp]
     lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
+    lib.vnm_stage_x.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
+    lib.vnm_spmm_staged.argtypes = [vp, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp]
+    lib.vnm_stage_x.restype = ci
+    lib.vnm_spmm_staged.restype = ci
     lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_workspace_bytes.restype = ci
     for f in (lib.vnm_query_sizes, lib.vnm_prune_compress, lib.vnm_pack, lib.vnm_spmm, lib.vnm_decompress,
@@ -174,6 +178,33 @@ def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO
         _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
         _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
         _ptr(ws), ws_bytes, _stream(X)), "vnm_spmm")
+    return Y
+
+
+def vnm_stage_x(X, M: int, staged=None):
+    """Re-lay X [T x in] for the matrix-core kernel; returns the staged uint8 tensor (reusable by
+    every layer with the same `in` and M)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    T, inn = X.shape
+    b = ctypes.c_int64(0)
+    _check(load_library().vnm_spmm_workspace_bytes(T, 64, inn, 64, 2, M, ctypes.byref(b)), "vnm_spmm_workspace_bytes")
+    if staged is None:
+        staged = torch.empty(max(b.value, 1), dtype=torch.uint8, device=X.device)
+    _check(load_library().vnm_stage_x(_ptr(X), T, X.stride(0) if T > 0 else inn, inn, M, _ptr(staged),
+                                      staged.numel(), _stream(X)), "vnm_stage_x")
+    return staged
+
+
+def vnm_spmm_staged(staged, T: int, c: Compressed, N: int = 2, out_dtype=None, Y=None):
+    """Y [T x out] from activations staged by vnm_stage_x and the packed weight of `c`."""
+    import torch
+    if Y is None:
+        Y = torch.empty((T, c.out), dtype=out_dtype or torch.float16, device=staged.device)
+    y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    _check(load_library().vnm_spmm_staged(_ptr(staged), T, _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y),
+                                          Y.stride(0) if T > 0 else c.out, y_dtype, _stream(staged)),
+           "vnm_spmm_staged")
     return Y
 
 

@@ -106,6 +106,35 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
   return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, st);
 }
 
+extern "C" int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, int M, void* staged,
+                           int64_t staged_bytes_given, void* stream) {
+  if (T != 0 && (!X || !staged)) return VNM_ERR_NULL;
+  if (in <= 0 || T < 0 || ldx < in) return VNM_ERR_SHAPE;
+  if (M < 4 || M > 16) return VNM_ERR_UNSUPPORTED;
+  if (T == 0) return VNM_OK;
+  const Dims d = make_dims(64, in, 64, M);                      // the staged layout depends on in and M only
+  if (!spmm_smfmac_applicable(X, ldx, d)) return VNM_ERR_UNSUPPORTED;
+  if (staged_bytes_given < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;
+  if ((uintptr_t)staged & 255) return VNM_ERR_ALIGN;
+  return launch_stage_x(X, T, ldx, d, staged, (hipStream_t)stream);
+}
+
+extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed, int64_t out,
+                               int64_t in, int V, int N, int M, void* Y, int64_t ldy, int y_dtype,
+                               void* stream) {
+  if (T != 0 && (!staged || !packed || !Y)) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (T < 0 || ldy < out) return VNM_ERR_SHAPE;
+  if (y_dtype != 0 && y_dtype != 1) return VNM_ERR_UNSUPPORTED;
+  if (!has_packed(V, M) || in % 8 != 0) return VNM_ERR_UNSUPPORTED;
+  if (((uintptr_t)staged & 255) || ((uintptr_t)packed & 255)) return VNM_ERR_ALIGN;
+  if ((uintptr_t)Y & (y_dtype == 0 ? 1 : 3)) return VNM_ERR_ALIGN;
+  if (T == 0) return VNM_OK;
+  return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype,
+                            (hipStream_t)stream);
+}
+
 extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
                                        int64_t* bytes) {
   if (!bytes) return VNM_ERR_NULL;

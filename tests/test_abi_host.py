@@ -23,7 +23,8 @@ def test_exports_every_declared_symbol(lib):
         text = f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(vnm_[a-z_]+)\s*\(", text))
-    assert {"vnm_query_sizes", "vnm_prune_compress", "vnm_pack", "vnm_spmm", "vnm_decompress",
+    assert {"vnm_query_sizes", "vnm_prune_compress", "vnm_pack", "vnm_spmm", "vnm_decompress", "vnm_stage_x",
+            "vnm_spmm_staged", "vnm_spmm_workspace_bytes",
             "vnm_status_string", "vnm_last_hip_error", "vnm_format_version"} <= names
     for n in names:
         assert hasattr(lib, n), n
@@ -75,6 +76,18 @@ def test_argument_errors(lib):
     assert lib.vnm_decompress(good, good, good, 128, 128, 64, 2, 8, good, 5, None) == 2
     assert lib.vnm_pack(good, good, good, 128, 128, 16, 2, 8, good, None) == 3
     assert lib.vnm_pack(good, good, good, 128, 128, 64, 2, 8, P(0x1008), None) == 4
+    # the matrix-core kernel needs its workspace: missing or short workspace is an error, not a silent fallback
+    a256 = P(0x1000)
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 5
+    assert lib.vnm_spmm(good, 4, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, a256, 16, None) == 5
+    b = ctypes.c_int64(-1)
+    assert lib.vnm_spmm_workspace_bytes(4096, 4096, 4096, 64, 2, 5, ctypes.byref(b)) == 0 and b.value == 32 * 103 * 13312
+    assert lib.vnm_spmm_workspace_bytes(16, 128, 128, 16, 2, 8, ctypes.byref(b)) == 0 and b.value == 0
+    assert lib.vnm_stage_x(good, 4, 100, 128, 5, a256, 1 << 30, None) == 2          # ldx < in
+    assert lib.vnm_stage_x(good, 4, 128, 128, 17, a256, 1 << 30, None) == 3         # M beyond the matrix-core range
+    assert lib.vnm_stage_x(good, 4, 128, 128, 5, a256, 16, None) == 5
+    assert lib.vnm_spmm_staged(a256, 4, None, 128, 128, 64, 2, 8, good, 128, 0, None) == 1
+    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 16, 2, 8, good, 128, 0, None) == 3
     assert lib.vnm_status_string(0) == b"ok" and b"null" in lib.vnm_status_string(1)
 
 

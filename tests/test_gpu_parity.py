@@ -159,6 +159,25 @@ def test_spmm_edge_cases():
     assert torch.equal(Y3, Ybig[:, :out])
 
 
+def test_stage_once_multiply_many():
+    """vnm_stage_x + vnm_spmm_staged equal vnm_spmm bit for bit, and one staging serves several
+    layers that share their input (as q/k/v or gate/up do)."""
+    rng = np.random.default_rng(21)
+    inn, T, V, M = 320, 300, 64, 5
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    Xd = _dev(X)
+    staged = vnm.vnm_stage_x(Xd, M)
+    for out in (128, 192):
+        W = _rand_w(rng, out, inn, "normal")
+        c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+        Y1 = vnm.vnm_spmm_staged(staged, T, c, out_dtype=torch.float32)
+        Y2 = vnm.vnm_spmm(Xd, c, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+        torch.cuda.synchronize()
+        assert torch.equal(Y1, Y2)
+        Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
+        assert orc.max_normalised_error(Y1.cpu().numpy(), Y_ref) <= TOL
+
+
 def test_spmm_pad_columns_are_never_read():
     """in = 72 at M = 5 pads to 75: the pad columns must count as zero even when the memory right
     after each X row holds NaN."""

@@ -9,167 +9,194 @@
 
 namespace vnm {
 
-__device__ __forceinline__ unsigned long long fp16_units_f(unsigned h) {
-  const unsigned bits = h & 0x7FFFu;
-  const unsigned e = bits >> 10, m = bits & 0x3FFu;
-  return e ? ((unsigned long long)(1024u + m) << (e - 1)) : (unsigned long long)m;
+// |w| of an fp16 bit pattern as a double.  A column sum of up to 128 such terms spans fewer than 53
+// bits, so every partial sum is exact in fp64 and the order of additions does not matter.
+__device__ __forceinline__ double fp16_abs_f64(unsigned h) {
+  const unsigned short b = (unsigned short)(h & 0x7FFFu);
+  _Float16 f;
+  __builtin_memcpy(&f, &b, 2);
+  return (double)f;
 }
 
-__device__ __forceinline__ unsigned top2_of_4_f(unsigned g0, unsigned g1, unsigned g2, unsigned g3) {
-  // (magnitude descending, position ascending): strict '>' while scanning upwards keeps the lowest
-  unsigned a = 0, ga = g0;
-  if (g1 > ga) { a = 1; ga = g1; }
-  if (g2 > ga) { a = 2; ga = g2; }
-  if (g3 > ga) { a = 3; ga = g3; }
-  unsigned b = (a == 0) ? 1u : 0u;
-  unsigned gb = (a == 0) ? g1 : g0;
-  if (a != 1 && b != 1 && g1 > gb) { b = 1; gb = g1; }
-  if (a != 2 && b != 2 && g2 > gb) { b = 2; gb = g2; }
-  if (a != 3 && b != 3 && g3 > gb) { b = 3; gb = g3; }
-  const unsigned p0 = a < b ? a : b, p1 = a < b ? b : a;
+// Two largest magnitudes of four, ties to the lower position (Section 3, row-wise N:4 step).
+// Each candidate becomes the key (magnitude, 3 - position, sign): distinct keys, larger is better.
+// Returns positions p0 < p1 as p0 | p1 << 2 and the two kept fp16 patterns in `pair` (p0 low half).
+__device__ __forceinline__ unsigned top2_of_4_f(unsigned w0, unsigned w1, unsigned w2, unsigned w3, unsigned& pair) {
+  const unsigned k0 = ((w0 & 0x7FFFu) << 3) | (3u << 1) | (w0 >> 15);
+  const unsigned k1 = ((w1 & 0x7FFFu) << 3) | (2u << 1) | (w1 >> 15);
+  const unsigned k2 = ((w2 & 0x7FFFu) << 3) | (1u << 1) | (w2 >> 15);
+  const unsigned k3 = ((w3 & 0x7FFFu) << 3) | (0u << 1) | (w3 >> 15);
+  const unsigned a = max(k0, k1), b = min(k0, k1), c = max(k2, k3), d = min(k2, k3);
+  const unsigned m1 = max(a, c);
+  const unsigned m2 = max(max(b, d), min(a, c));
+  const unsigned pa = 3u - ((m1 >> 1) & 3u), pb = 3u - ((m2 >> 1) & 3u);
+  const unsigned va = (m1 >> 3) | ((m1 & 1u) << 15), vb = (m2 >> 3) | ((m2 & 1u) << 15);
+  const bool sw = pa > pb;
+  const unsigned p0 = sw ? pb : pa, p1 = sw ? pa : pb;
+  pair = sw ? (vb | (va << 16)) : (va | (vb << 16));
   return p0 | (p1 << 2);
 }
 
-// LDS layout (dynamic): tile u16 [V][NCP] | sums u64 [G][NC] | keep u8 [NBW][4] | pairs u32 [V][NBW] | nibs u8 [V][NBW]
 struct PruneFastArgs {
   const unsigned short* W; int64_t ldw, out, in;
   int V, M; int64_t R, B, S;
-  int KSW;                 // K steps per workgroup
+  int KSW;                 // K steps (8 column blocks each) per workgroup
+  int G;                   // row groups that sum columns in parallel
   unsigned short* values; unsigned char* meta; unsigned char* colidx; unsigned char* mask;
   uint4* pa; unsigned short* pidx; unsigned* pcol;   // matrix-core copy or null
 };
 
+// LDS layout (dynamic): tile u16 [V][NCP] | part f64 [G][NC] | tot f64 [NC] | keep u32 [NBW] | nibs u8 [V][NBW] (mask only)
 __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int V = a.V, M = a.M;
-  const int64_t r = blockIdx.y;
-  const int64_t s_begin = (int64_t)blockIdx.x * a.KSW;
+  const int64_t r = blockIdx.x;
+  const int64_t s_begin = (int64_t)blockIdx.y * a.KSW;
   const int nks = (int)((a.S - s_begin) < a.KSW ? (a.S - s_begin) : a.KSW);
-  const int NCmax = a.KSW * 8 * M, NBWmax = a.KSW * 8;
-  const int NC = nks * 8 * M;                       // raw columns of this workgroup (padded space)
+  const int NC = a.KSW * 8 * M, NBW = a.KSW * 8;    // columns / blocks of a full span
   const int64_t c0 = s_begin * 8 * M;
   const int64_t b0 = s_begin * 8;
   const int nbw = (int)((a.B - b0) < nks * 8 ? (a.B - b0) : nks * 8);   // real blocks here
-  const int NCP = NCmax + 8;                        // tile pitch in elements (16-byte rows, skewed banks)
-  const int G = 256 / NCmax > 0 ? 256 / NCmax : 1;  // row groups for the column sums
+  const int NCP = NC + 8;                           // tile pitch in elements (16-byte rows, skewed banks)
+  const int G = a.G;
   unsigned short* tile = (unsigned short*)smem;
-  unsigned long long* sums = (unsigned long long*)(smem + (((size_t)V * NCP * 2 + 15) & ~(size_t)15));
-  unsigned char* keep = (unsigned char*)(sums + (size_t)G * NCmax);
-  unsigned* pairs = (unsigned*)(keep + (((size_t)NBWmax * 4 + 15) & ~(size_t)15));
-  unsigned char* nibs = (unsigned char*)(pairs + (size_t)V * NBWmax);
+  double* part = (double*)(smem + (size_t)V * NCP * 2);
+  double* tot = part + (size_t)G * NC;
+  unsigned* keep = (unsigned*)(tot + NC);
+  unsigned char* nibs = (unsigned char*)(keep + NBW);
   const int tid = threadIdx.x;
-
-  // phase 0: W tile -> LDS, 16 bytes per access, zero where W is padded
   const int chunks = NC / 8;
-  for (int item = tid; item < V * chunks; item += 256) {
-    const int v = item / chunks, ch = item - v * chunks;
-    const int64_t row = r * V + v, col = c0 + ch * 8;
-    uint4 w = make_uint4(0, 0, 0, 0);
-    if (row < a.out && col < a.in) w = *(const uint4*)(a.W + row * a.ldw + col);
-    *(uint4*)(tile + (size_t)v * NCP + ch * 8) = w;
-  }
-  __syncthreads();
-  // phase 1: exact column sums, G row groups in parallel
-  {
-    const int g = tid / NC, c = tid - g * NC;
-    if (g < G) {
-      const int v0 = (V * g) / G, v1 = (V * (g + 1)) / G;
-      unsigned long long acc = 0;
-      for (int v = v0; v < v1; ++v) acc += fp16_units_f(tile[(size_t)v * NCP + c]);
-      sums[(size_t)g * NCmax + c] = acc;
-    }
-  }
-  __syncthreads();
-  // phase 2: per block keep the 4 largest column sums (ties to the lower index), ascending
-  for (int b = tid; b < nks * 8; b += 256) {
-    unsigned long long L[16];
-    for (int c = 0; c < M; ++c) {
-      unsigned long long t = 0;
-      for (int g = 0; g < G; ++g) t += sums[(size_t)g * NCmax + b * M + c];
-      L[c] = t;
-    }
-    int ch[4] = {-1, -1, -1, -1};
-    for (int k = 0; k < 4; ++k) {
-      int best = -1;
-      for (int c = 0; c < M; ++c) {
-        if (c == ch[0] || c == ch[1] || c == ch[2]) continue;
-        if (best < 0 || L[c] > L[best]) best = c;
+
+  // phase 0: W tile -> LDS with 16-byte accesses (zero where W is padded); the same registers feed
+  // the partial column sums: thread (g, ch) owns 8 columns and the rows g, g + G, g + 2G, ...
+  if (tid < chunks * G) {
+    const int g = tid / chunks, ch = tid - g * chunks;
+    const int64_t col = c0 + ch * 8;
+    const bool col_ok = col < a.in;
+    double acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+    for (int v = g; v < V; v += 4 * G) {
+      uint4 w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int vv = v + u * G;
+        const int64_t row = r * V + vv;
+        w[u] = make_uint4(0, 0, 0, 0);
+        if (vv < V && row < a.out && col_ok) w[u] = *(const uint4*)(a.W + row * a.ldw + col);
       }
-      ch[k] = best;
-    }
-#define VNM_CSWAP(i, j) { if (ch[i] > ch[j]) { int t_ = ch[i]; ch[i] = ch[j]; ch[j] = t_; } }
-    VNM_CSWAP(0, 1) VNM_CSWAP(2, 3) VNM_CSWAP(0, 2) VNM_CSWAP(1, 3) VNM_CSWAP(1, 2)
-#undef VNM_CSWAP
-    for (int k = 0; k < 4; ++k) keep[b * 4 + k] = (unsigned char)ch[k];
-    if (b < nbw)
-      *(uchar4*)(a.colidx + (r * a.B + b0 + b) * 4) =
-          make_uchar4((unsigned char)ch[0], (unsigned char)ch[1], (unsigned char)ch[2], (unsigned char)ch[3]);
-  }
-  __syncthreads();
-  // phase 3: per (row, block) keep the 2 largest magnitudes of the 4 kept columns
-  const int64_t vrow_elems = 2 * a.B;
-  for (int idx = tid; idx < V * nks * 8; idx += 256) {
-    const int v = idx / (nks * 8), b = idx - v * (nks * 8);
-    const unsigned short* trow = tile + (size_t)v * NCP + b * M;
-    const unsigned w0 = trow[keep[b * 4 + 0]], w1 = trow[keep[b * 4 + 1]], w2 = trow[keep[b * 4 + 2]],
-                   w3 = trow[keep[b * 4 + 3]];
-    const unsigned nib = top2_of_4_f(w0 & 0x7FFFu, w1 & 0x7FFFu, w2 & 0x7FFFu, w3 & 0x7FFFu);
-    const unsigned p0 = nib & 3, p1 = nib >> 2;
-    const unsigned k0 = p0 == 0 ? w0 : p0 == 1 ? w1 : w2;            // p0 <= 2
-    const unsigned k1 = p1 == 1 ? w1 : p1 == 2 ? w2 : w3;            // p1 >= 1
-    const unsigned pair = k0 | (k1 << 16);
-    pairs[(size_t)v * NBWmax + b] = pair;
-    nibs[(size_t)v * NBWmax + b] = (unsigned char)nib;
-    if (b < nbw) *(unsigned*)(a.values + (r * V + v) * vrow_elems + 2 * (b0 + b)) = pair;
-  }
-  __syncthreads();
-  // phase 4: canonical meta bytes (two blocks per byte; b0 is a multiple of 8)
-  {
-    const int nbytes = (nbw + 1) / 2;
-    const int64_t mrow = (a.B + 1) / 2;
-    for (int idx = tid; idx < V * nbytes; idx += 256) {
-      const int v = idx / nbytes, j = idx - v * nbytes;
-      const unsigned lo = nibs[(size_t)v * NBWmax + 2 * j];
-      const unsigned hi = (2 * j + 1 < nbw) ? nibs[(size_t)v * NBWmax + 2 * j + 1] : 0u;
-      a.meta[(r * V + v) * mrow + b0 / 2 + j] = (unsigned char)(lo | (hi << 4));
-    }
-  }
-  // phase 5: matrix-core copy.  In a 32-row tile lane l = i + 32 h holds row i; its 8 values are the
-  // kept pairs of blocks 4h .. 4h+3 of the K step; 2-bit positions at bits [2e+1 : 2e].
-  if (a.pa) {
-    const int tiles = V / 32;
-    for (int idx = tid; idx < nks * tiles * 64; idx += 256) {
-      const int lane = idx & 63;
-      const int at = (idx >> 6) % tiles, ks = (idx >> 6) / tiles;
-      const int i = lane & 31, h = lane >> 5;
-      const int v = at * 32 + i;
-      const unsigned* pr = pairs + (size_t)v * NBWmax + ks * 8 + 4 * h;
-      const unsigned char* nb = nibs + (size_t)v * NBWmax + ks * 8 + 4 * h;
-      uint4 q = make_uint4(pr[0], pr[1], pr[2], pr[3]);
-      unsigned ix = (unsigned)nb[0] | ((unsigned)nb[1] << 4) | ((unsigned)nb[2] << 8) | ((unsigned)nb[3] << 12);
-      // blocks beyond the last real one: value 0, positions (0, 1)
-      for (int g = 0; g < 4; ++g)
-        if (ks * 8 + 4 * h + g >= nbw) {
-          ((unsigned*)&q)[g] = 0;
-          ix = (ix & ~(15u << (4 * g))) | (4u << (4 * g));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int vv = v + u * G;
+        if (vv < V) {
+          *(uint4*)(tile + (size_t)vv * NCP + ch * 8) = w[u];
+          const unsigned d[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += fp16_abs_f64(d[e] & 0xFFFFu);
+            acc[2 * e + 1] += fp16_abs_f64(d[e] >> 16);
+          }
         }
-      const int64_t rs = r * a.S + s_begin + ks;
-      a.pa[(rs * tiles + at) * 64 + lane] = q;
-      a.pidx[(rs * 64 + lane) * tiles + at] = (unsigned short)ix;
+      }
     }
+    double2* pp = (double2*)(part + (size_t)g * NC + ch * 8);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pp[e] = make_double2(acc[2 * e], acc[2 * e + 1]);
+  }
+  __syncthreads();
+  // phase 1: column totals
+  for (int c = tid; c < NC; c += 256) {
+    double t = 0.0;
+    for (int g = 0; g < G; ++g) t += part[(size_t)g * NC + c];
+    tot[c] = t;
+  }
+  __syncthreads();
+  // phase 2: per block keep the 4 columns of largest L1 norm (ties to the lower index), ascending:
+  // column c is kept when fewer than 4 columns beat it
+  for (int b = tid; b < NBW; b += 256) {
+    double L[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) L[c] = c < M ? tot[b * M + c] : -1.0;
+    unsigned kp = 0; int nk = 0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      int rank = 0;
+#pragma unroll
+      for (int o = 0; o < 16; ++o) rank += (o < c) ? (L[o] >= L[c]) : (L[o] > L[c]);
+      if (c < M && rank < 4) { kp |= (unsigned)c << (8 * nk); ++nk; }
+    }
+    keep[b] = kp;
+    if (b < nbw) *(unsigned*)(a.colidx + (r * a.B + b0 + b) * 4) = kp;
+  }
+  __syncthreads();
+  // phase 3: per (row, block) keep the 2 largest magnitudes of the 4 kept columns, and emit the
+  // canonical triple and the matrix-core copy.  An item is one lane of one K step in the layout of
+  // the sparse matrix instruction: lane l = i + 32 h holds, for every 32-row tile, row i and the
+  // kept pairs of blocks 4h .. 4h+3; 2-bit positions at bits [2e+1 : 2e].
+  const int tiles = V / 32 > 0 ? V / 32 : 1;
+  const int64_t vrow_elems = 2 * a.B;
+  const int64_t mrow = (a.B + 1) / 2;
+  const bool v16 = (a.B & 3) == 0;
+  for (int item = tid; item < nks * 64; item += 256) {
+    const int ks = item >> 6, lane = item & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int blk0 = ks * 8 + 4 * h;
+    const uint4 kp4 = *(const uint4*)(keep + blk0);
+    const unsigned kp[4] = {kp4.x, kp4.y, kp4.z, kp4.w};
+    const int64_t rs = r * a.S + s_begin + ks;
+    unsigned short ixs[4] = {0, 0, 0, 0};
+    for (int at = 0; at < tiles; ++at) {
+      const int v = at * 32 + i;
+      if (v >= V) break;
+      const unsigned short* trow = tile + (size_t)v * NCP + blk0 * M;
+      unsigned q[4], ix = 0;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const unsigned short* tb = trow + g * M;
+        const unsigned w0 = tb[kp[g] & 255u], w1 = tb[(kp[g] >> 8) & 255u], w2 = tb[(kp[g] >> 16) & 255u],
+                       w3 = tb[kp[g] >> 24];
+        const unsigned nib = top2_of_4_f(w0, w1, w2, w3, q[g]);
+        ix |= nib << (4 * g);
+      }
+      ixs[at] = (unsigned short)ix;
+      const int64_t row = r * V + v;
+      unsigned short* vdst = a.values + row * vrow_elems + 2 * (b0 + blk0);
+      if (v16 && blk0 + 4 <= nbw) {
+        *(uint4*)vdst = make_uint4(q[0], q[1], q[2], q[3]);
+      } else {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (blk0 + g < nbw) *(unsigned*)(vdst + 2 * g) = q[g];
+      }
+      unsigned char* mdst = a.meta + row * mrow + ((b0 + blk0) >> 1);
+      if (blk0 < nbw) mdst[0] = (unsigned char)((ix & 15u) | (blk0 + 1 < nbw ? (ix & 0xF0u) : 0u));
+      if (blk0 + 2 < nbw) mdst[1] = (unsigned char)(((ix >> 8) & 15u) | (blk0 + 3 < nbw ? ((ix >> 8) & 0xF0u) : 0u));
+      if (a.pa) a.pa[(rs * tiles + at) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
+      if (a.mask) *(unsigned*)(nibs + (size_t)v * NBW + blk0) =
+          (ix & 15u) | ((ix & 0xF0u) << 4) | ((ix & 0xF00u) << 8) | ((ix & 0xF000u) << 12);
+    }
+    if (a.pa && V >= 32) {
+      unsigned short* pd = a.pidx + (rs * 64 + lane) * tiles;
+      if (tiles == 1) pd[0] = ixs[0];
+      else if (tiles == 2) *(unsigned*)pd = (unsigned)ixs[0] | ((unsigned)ixs[1] << 16);
+      else *(uint2*)pd = make_uint2((unsigned)ixs[0] | ((unsigned)ixs[1] << 16), (unsigned)ixs[2] | ((unsigned)ixs[3] << 16));
+    }
+  }
+  if (a.pa) {
     for (int idx = tid; idx < nks * 8; idx += 256) {
       const int kq = idx & 3, h = (idx >> 2) & 1, ks = idx >> 3;
       unsigned o = 0;
       for (int m = 0; m < 4; ++m) {
         const int blk = 4 * (m >> 1) + 2 * h + (m & 1);
-        const unsigned c = (ks * 8 + blk < nbw) ? keep[(ks * 8 + blk) * 4 + kq] : (unsigned)kq;
+        const unsigned c = (keep[ks * 8 + blk] >> (8 * kq)) & 255u;
         o |= (unsigned)(blk * M + c) << (8 * m);
       }
       a.pcol[(r * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
     }
   }
-  // phase 6: optional dense 0-1 mask
+  // phase 4: optional dense 0-1 mask
   if (a.mask) {
+    __syncthreads();
     for (int item = tid; item < V * chunks; item += 256) {
       const int v = item / chunks, ch = item - v * chunks;
       const int64_t row = r * V + v, col = c0 + ch * 8;
@@ -177,8 +204,9 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         unsigned char mk[8];
         for (int e = 0; e < 8; ++e) {
           const int c = ch * 8 + e, b = c / M, ci = c - b * M;
-          const unsigned nib = nibs[(size_t)v * NBWmax + b];
-          mk[e] = (keep[b * 4 + (nib & 3)] == ci) | (keep[b * 4 + (nib >> 2)] == ci);
+          const unsigned nib = nibs[(size_t)v * NBW + b];
+          const unsigned kp = keep[b];
+          mk[e] = (((kp >> (8 * (nib & 3))) & 255u) == (unsigned)ci) | (((kp >> (8 * (nib >> 2))) & 255u) == (unsigned)ci);
         }
         *(uint2*)(a.mask + row * a.in + col) = *(const uint2*)mk;
       }
@@ -186,19 +214,23 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   }
 }
 
-static size_t prune_fast_lds(int V, int M, int KSW) {
+static int prune_fast_ksw(int V, int M) {
+  int k = 8;
+  while (k > 1 && (size_t)V * (k * 8 * M + 8) * 2 > 46 * 1024) k >>= 1;
+  return k;
+}
+
+static size_t prune_fast_lds(int V, int M, int KSW, int G, bool mask) {
   const size_t NC = (size_t)KSW * 8 * M, NBW = (size_t)KSW * 8;
-  const size_t G = 256 / NC > 0 ? 256 / NC : 1;
-  size_t b = ((size_t)V * (NC + 8) * 2 + 15) & ~(size_t)15;
-  b += G * NC * 8;
-  b += (NBW * 4 + 15) & ~(size_t)15;
-  b += (size_t)V * NBW * 4 + (size_t)V * NBW;
+  size_t b = (size_t)V * (NC + 8) * 2;
+  b += (size_t)G * NC * 8 + NC * 8 + NBW * 4;
+  if (mask) b += (size_t)V * NBW;
   return b;
 }
 
 bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask) {
-  return d.M <= 16 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W & 15) == 0 && d.R <= 65535 &&
-         (!mask || ((uintptr_t)mask & 7) == 0);
+  return d.M <= 16 && d.V % 32 == 0 && d.V <= 128 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W & 15) == 0 &&
+         d.S <= 65535 && (!mask || ((uintptr_t)mask & 7) == 0);
 }
 
 int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, void* meta, void* colidx,
@@ -206,7 +238,9 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
   PruneFastArgs a;
   a.W = (const unsigned short*)W; a.ldw = ldw; a.out = d.out; a.in = d.in; a.V = d.V; a.M = d.M;
   a.R = d.R; a.B = d.B; a.S = d.S;
-  a.KSW = 128 / (8 * d.M) > 0 ? 128 / (8 * d.M) : 1;
+  a.KSW = prune_fast_ksw(d.V, d.M);
+  const int chunks = a.KSW * d.M;
+  a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
   a.values = (unsigned short*)values; a.meta = (unsigned char*)meta; a.colidx = (unsigned char*)colidx;
   a.mask = (unsigned char*)mask;
   a.pa = nullptr; a.pidx = nullptr; a.pcol = nullptr;
@@ -215,14 +249,16 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
     char* p = (char*)packed;
     a.pa = (uint4*)(p + pl.pa_off); a.pidx = (unsigned short*)(p + pl.pidx_off); a.pcol = (unsigned*)(p + pl.pcol_off);
   }
-  const size_t lds = prune_fast_lds(d.V, d.M, a.KSW);
+  const size_t lds = prune_fast_lds(d.V, d.M, a.KSW, a.G, mask != nullptr);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)prune_pack_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(prune_pack)"); return VNM_ERR_HIP; }
     attr_set = true;
   }
-  dim3 grid((unsigned)((d.S + a.KSW - 1) / a.KSW), (unsigned)d.R);
+  // row blocks along x: workgroups that share a span of columns' cache lines with their
+  // neighbours in y sit R apart in launch order
+  dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
   hipLaunchKernelGGL(prune_pack_kernel, grid, dim3(256), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "prune_pack_kernel"); return VNM_ERR_HIP; }

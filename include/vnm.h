@@ -82,8 +82,8 @@ int vnm_query_sizes(int64_t out, int64_t in, int V, int N, int M, vnm_sizes* s);
  *   values, meta, colidx   dev outputs, sizes from vnm_query_sizes
  *   mask     dev u8 [out x in] (dense, leading dimension in) or NULL: the 0-1 mask of Section 3
  *   packed   dev, packed_bytes, 256-byte aligned, or NULL
- * Column norms are accumulated exactly (integer fixed point), so the result does not depend on any
- * summation order.  Non-finite weights are not supported (result unspecified, no fault).
+ * Column norms are accumulated exactly (integer fixed point, or fp64 where every partial sum is
+ * representable), so the result does not depend on any summation order.  Non-finite weights are not supported (result unspecified, no fault).
  */
 int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_t ldw, int V, int N, int M,
                        void* values, void* meta, void* colidx, void* mask, void* packed,

@@ -55,7 +55,7 @@ extern "C" int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_
     if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
   }
   hipStream_t st = (hipStream_t)stream;
-  if (prune_fast_applicable(W, ldw, d, mask) && (!packed || has_packed(V, M)))
+  if (prune_fast_applicable(W, ldw, d, mask) && ((uintptr_t)colidx & 3) == 0 && (!packed || has_packed(V, M)))
     return launch_prune_fast(W, ldw, d, values, meta, colidx, mask, packed, st);
   rc = launch_prune_compress(W, ldw, d, values, meta, colidx, mask, st);
   if (rc) return rc;
@@ -154,7 +154,7 @@ extern "C" int vnm_decompress(const void* values, const void* meta, const void* 
   if (ldw < in) return VNM_ERR_SHAPE;
   if (((uintptr_t)W_out & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
   const Dims d = make_dims(out, in, V, M);
-  if (decompress_fast_applicable(W_out, ldw, d))
+  if (decompress_fast_applicable(W_out, ldw, d) && ((uintptr_t)colidx & 3) == 0)
     return launch_decompress_fast(values, meta, colidx, d, W_out, ldw, (hipStream_t)stream);
   return launch_decompress(values, meta, colidx, d, W_out, ldw, (hipStream_t)stream);
 }

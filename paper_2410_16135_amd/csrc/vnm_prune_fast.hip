@@ -6,6 +6,7 @@
 // vnm_prune.hip: column L1 norms are exact integer sums of the fp16 magnitudes, ties go to the
 // lower index.
 #include "vnm_internal.h"
+#include <cstdlib>
 
 namespace vnm {
 
@@ -46,7 +47,7 @@ struct PruneFastArgs {
   uint4* pa; unsigned short* pidx; unsigned* pcol;   // matrix-core copy or null
 };
 
-// LDS layout (dynamic): tile u16 [V][NCP] | part f64 [G][NC] | tot f64 [NC] | keep u32 [NBW] | nibs u8 [V][NBW] (mask only)
+// LDS layout (dynamic): tile u16 [V][NCP] | tot f64 [NC] | keep u32 [NBW]
 __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int V = a.V, M = a.M;
@@ -60,15 +61,16 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   const int NCP = NC + 8;                           // tile pitch in elements (16-byte rows, skewed banks)
   const int G = a.G;
   unsigned short* tile = (unsigned short*)smem;
-  double* part = (double*)(smem + (size_t)V * NCP * 2);
-  double* tot = part + (size_t)G * NC;
+  double* tot = (double*)(smem + (size_t)V * NCP * 2);
   unsigned* keep = (unsigned*)(tot + NC);
-  unsigned char* nibs = (unsigned char*)(keep + NBW);
   const int tid = threadIdx.x;
   const int chunks = NC / 8;
 
+  for (int c = tid; c < NC; c += 256) tot[c] = 0.0;
+  __syncthreads();
   // phase 0: W tile -> LDS with 16-byte accesses (zero where W is padded); the same registers feed
-  // the partial column sums: thread (g, ch) owns 8 columns and the rows g, g + G, g + 2G, ...
+  // the column sums: thread (g, ch) owns 8 columns and the rows g, g + G, g + 2G, ...; the partial
+  // sums meet in LDS by atomic adds (exact, so their order is immaterial)
   if (tid < chunks * G) {
     const int g = tid / chunks, ch = tid - g * chunks;
     const int64_t col = c0 + ch * 8;
@@ -76,17 +78,18 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
     double acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.0;
-    for (int v = g; v < V; v += 4 * G) {
-      uint4 w[4];
+    constexpr int kBatch = 12;
+    for (int v = g; v < V; v += kBatch * G) {
+      uint4 w[kBatch];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kBatch; ++u) {
         const int vv = v + u * G;
         const int64_t row = r * V + vv;
         w[u] = make_uint4(0, 0, 0, 0);
         if (vv < V && row < a.out && col_ok) w[u] = *(const uint4*)(a.W + row * a.ldw + col);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kBatch; ++u) {
         const int vv = v + u * G;
         if (vv < V) {
           *(uint4*)(tile + (size_t)vv * NCP + ch * 8) = w[u];
@@ -99,44 +102,32 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         }
       }
     }
-    double2* pp = (double2*)(part + (size_t)g * NC + ch * 8);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) pp[e] = make_double2(acc[2 * e], acc[2 * e + 1]);
+    for (int e = 0; e < 8; ++e) unsafeAtomicAdd(tot + ch * 8 + e, acc[e]);
   }
   __syncthreads();
-  // phase 1: column totals
-  for (int c = tid; c < NC; c += 256) {
-    double t = 0.0;
-    for (int g = 0; g < G; ++g) t += part[(size_t)g * NC + c];
-    tot[c] = t;
-  }
-  __syncthreads();
-  // phase 2: per block keep the 4 columns of largest L1 norm (ties to the lower index), ascending:
+  // phase 1: per block keep the 4 columns of largest L1 norm (ties to the lower index), ascending:
   // column c is kept when fewer than 4 columns beat it
   for (int b = tid; b < NBW; b += 256) {
-    double L[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) L[c] = c < M ? tot[b * M + c] : -1.0;
+    const double* L = tot + b * M;
     unsigned kp = 0; int nk = 0;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
+    for (int c = 0; c < M; ++c) {
+      const double Lc = L[c];
       int rank = 0;
-#pragma unroll
-      for (int o = 0; o < 16; ++o) rank += (o < c) ? (L[o] >= L[c]) : (L[o] > L[c]);
-      if (c < M && rank < 4) { kp |= (unsigned)c << (8 * nk); ++nk; }
+      for (int o = 0; o < c; ++o) rank += L[o] >= Lc;
+      for (int o = c + 1; o < M; ++o) rank += L[o] > Lc;
+      if (rank < 4) { kp |= (unsigned)c << (8 * nk); ++nk; }
     }
     keep[b] = kp;
     if (b < nbw) *(unsigned*)(a.colidx + (r * a.B + b0 + b) * 4) = kp;
   }
   __syncthreads();
-  // phase 3: per (row, block) keep the 2 largest magnitudes of the 4 kept columns, and emit the
-  // canonical triple and the matrix-core copy.  An item is one lane of one K step in the layout of
-  // the sparse matrix instruction: lane l = i + 32 h holds, for every 32-row tile, row i and the
-  // kept pairs of blocks 4h .. 4h+3; 2-bit positions at bits [2e+1 : 2e].
-  const int tiles = V / 32 > 0 ? V / 32 : 1;
-  const int64_t vrow_elems = 2 * a.B;
-  const int64_t mrow = (a.B + 1) / 2;
-  const bool v16 = (a.B & 3) == 0;
+  // phase 2: per (row, block) keep the 2 largest magnitudes of the 4 kept columns.  An item is one
+  // lane of one K step in the layout of the sparse matrix instruction: lane l = i + 32 h holds, for
+  // every 32-row tile, row i and the kept pairs of blocks 4h .. 4h+3; 2-bit positions at bits
+  // [2e+1 : 2e].  The matrix-core copy is stored from here; the canonical values and metadata of
+  // the four blocks are parked in the tile, over the 4M elements they came from, for phase 3.
+  const int tiles = V / 32;
   for (int item = tid; item < nks * 64; item += 256) {
     const int ks = item >> 6, lane = item & 63;
     const int i = lane & 31, h = lane >> 5;
@@ -147,8 +138,7 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
     unsigned short ixs[4] = {0, 0, 0, 0};
     for (int at = 0; at < tiles; ++at) {
       const int v = at * 32 + i;
-      if (v >= V) break;
-      const unsigned short* trow = tile + (size_t)v * NCP + blk0 * M;
+      unsigned short* trow = tile + (size_t)v * NCP + blk0 * M;
       unsigned q[4], ix = 0;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -159,27 +149,53 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         ix |= nib << (4 * g);
       }
       ixs[at] = (unsigned short)ix;
-      const int64_t row = r * V + v;
-      unsigned short* vdst = a.values + row * vrow_elems + 2 * (b0 + blk0);
-      if (v16 && blk0 + 4 <= nbw) {
-        *(uint4*)vdst = make_uint4(q[0], q[1], q[2], q[3]);
-      } else {
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          if (blk0 + g < nbw) *(unsigned*)(vdst + 2 * g) = q[g];
-      }
-      unsigned char* mdst = a.meta + row * mrow + ((b0 + blk0) >> 1);
-      if (blk0 < nbw) mdst[0] = (unsigned char)((ix & 15u) | (blk0 + 1 < nbw ? (ix & 0xF0u) : 0u));
-      if (blk0 + 2 < nbw) mdst[1] = (unsigned char)(((ix >> 8) & 15u) | (blk0 + 3 < nbw ? ((ix >> 8) & 0xF0u) : 0u));
       if (a.pa) a.pa[(rs * tiles + at) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
-      if (a.mask) *(unsigned*)(nibs + (size_t)v * NBW + blk0) =
-          (ix & 15u) | ((ix & 0xF0u) << 4) | ((ix & 0xF00u) << 8) | ((ix & 0xF000u) << 12);
+      // 8-byte aligned: blk0 is a multiple of 4
+      *(uint2*)trow = make_uint2(q[0], q[1]);
+      *(uint2*)(trow + 4) = make_uint2(q[2], q[3]);
+      trow[8] = (unsigned short)ix;
     }
-    if (a.pa && V >= 32) {
+    if (a.pa) {
       unsigned short* pd = a.pidx + (rs * 64 + lane) * tiles;
       if (tiles == 1) pd[0] = ixs[0];
       else if (tiles == 2) *(unsigned*)pd = (unsigned)ixs[0] | ((unsigned)ixs[1] << 16);
       else *(uint2*)pd = make_uint2((unsigned)ixs[0] | ((unsigned)ixs[1] << 16), (unsigned)ixs[2] | ((unsigned)ixs[3] << 16));
+    }
+  }
+  __syncthreads();
+  // phase 3: canonical values and metadata, a row's pieces stored by neighbouring lanes
+  {
+    const int64_t vrow_elems = 2 * a.B;
+    const int64_t mrow = (a.B + 1) / 2;
+    const bool v16 = (a.B & 3) == 0 && ((uintptr_t)a.values & 15) == 0;
+    const int nq = nks * 2;                                  // groups of 4 blocks in this span
+    const unsigned nq_inv = (65536u + nq - 1) / nq;
+    for (int item = tid; item < V * nq; item += 256) {
+      const int v = (int)(((unsigned)item * nq_inv) >> 16), qd = item - v * nq;   // item < 2^12, nq <= 16: exact
+      const int blk0 = qd * 4;
+      if (blk0 >= nbw) continue;
+      const unsigned short* trow = tile + (size_t)v * NCP + blk0 * M;
+      const uint2 lo = *(const uint2*)trow, hi = *(const uint2*)(trow + 4);
+      const unsigned ix = trow[8];
+      const int64_t row = r * V + v;
+      unsigned short* vdst = a.values + row * vrow_elems + 2 * (b0 + blk0);
+      if (v16 && blk0 + 4 <= nbw) {
+        *(uint4*)vdst = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      } else {
+        *(unsigned*)vdst = lo.x;
+        if (blk0 + 1 < nbw) *(unsigned*)(vdst + 2) = lo.y;
+        if (blk0 + 2 < nbw) *(unsigned*)(vdst + 4) = hi.x;
+        if (blk0 + 3 < nbw) *(unsigned*)(vdst + 6) = hi.y;
+      }
+      // two blocks per byte; a block beyond the last real one leaves its nibble zero
+      unsigned char* mdst = a.meta + row * mrow + ((b0 + blk0) >> 1);
+      if (blk0 + 4 <= nbw) {
+        const unsigned short two = (unsigned short)ix;
+        __builtin_memcpy(mdst, &two, 2);
+      } else {
+        mdst[0] = (unsigned char)((ix & 15u) | (blk0 + 1 < nbw ? (ix & 0xF0u) : 0u));
+        if (blk0 + 2 < nbw) mdst[1] = (unsigned char)(((ix >> 8) & 15u) | (blk0 + 3 < nbw ? ((ix >> 8) & 0xF0u) : 0u));
+      }
     }
   }
   if (a.pa) {
@@ -194,43 +210,42 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
       a.pcol[(r * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
     }
   }
-  // phase 4: optional dense 0-1 mask
+  // phase 4: optional dense 0-1 mask, from the positions parked in the tile
   if (a.mask) {
-    __syncthreads();
-    for (int item = tid; item < V * chunks; item += 256) {
-      const int v = item / chunks, ch = item - v * chunks;
-      const int64_t row = r * V + v, col = c0 + ch * 8;
-      if (row < a.out && col < a.in) {
-        unsigned char mk[8];
-        for (int e = 0; e < 8; ++e) {
-          const int c = ch * 8 + e, b = c / M, ci = c - b * M;
-          const unsigned nib = nibs[(size_t)v * NBW + b];
-          const unsigned kp = keep[b];
-          mk[e] = (((kp >> (8 * (nib & 3))) & 255u) == (unsigned)ci) | (((kp >> (8 * (nib >> 2))) & 255u) == (unsigned)ci);
-        }
-        *(uint2*)(a.mask + row * a.in + col) = *(const uint2*)mk;
-      }
+    for (int item = tid; item < V * NBW; item += 256) {
+      const int v = item / NBW, b = item - v * NBW;
+      if (b >= nbw) continue;
+      const int64_t row = r * V + v;
+      if (row >= a.out) continue;
+      const unsigned ix = tile[(size_t)v * NCP + (b & ~3) * M + 8];
+      const unsigned nib = (ix >> (4 * (b & 3))) & 15u;
+      const unsigned kp = keep[b];
+      const unsigned ca = (kp >> (8 * (nib & 3))) & 255u, cb = (kp >> (8 * (nib >> 2))) & 255u;
+      const int64_t colb = (b0 + b) * M;
+      for (int c = 0; c < M; ++c)
+        if (colb + c < a.in) a.mask[row * a.in + colb + c] = (unsigned char)((unsigned)c == ca || (unsigned)c == cb);
     }
   }
 }
 
-static int prune_fast_ksw(int V, int M) {
+// K steps per workgroup: 8 make every span of columns a whole number of 128-byte lines; fewer when
+// the tile would not leave room for 3 workgroups per CU, or when the launch would be little more
+// than one generation of workgroups on the 256 CUs (then shorter-lived workgroups overlap better).
+static int prune_fast_ksw(const Dims& d) {
   int k = 8;
-  while (k > 1 && (size_t)V * (k * 8 * M + 8) * 2 > 46 * 1024) k >>= 1;
+  while (k > 1 && (size_t)d.V * (k * 8 * d.M + 8) * 2 > 46 * 1024) k >>= 1;
+  while (k > 4 && d.R * ((d.S + k - 1) / k) < 6 * 256) k >>= 1;
   return k;
 }
 
-static size_t prune_fast_lds(int V, int M, int KSW, int G, bool mask) {
+static size_t prune_fast_lds(int V, int M, int KSW) {
   const size_t NC = (size_t)KSW * 8 * M, NBW = (size_t)KSW * 8;
-  size_t b = (size_t)V * (NC + 8) * 2;
-  b += (size_t)G * NC * 8 + NC * 8 + NBW * 4;
-  if (mask) b += (size_t)V * NBW;
-  return b;
+  return (size_t)V * (NC + 8) * 2 + NC * 8 + NBW * 4;
 }
 
 bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask) {
   return d.M <= 16 && d.V % 32 == 0 && d.V <= 128 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W & 15) == 0 &&
-         d.S <= 65535 && (!mask || ((uintptr_t)mask & 7) == 0);
+         d.S <= 65535;
 }
 
 int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, void* meta, void* colidx,
@@ -238,7 +253,8 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
   PruneFastArgs a;
   a.W = (const unsigned short*)W; a.ldw = ldw; a.out = d.out; a.in = d.in; a.V = d.V; a.M = d.M;
   a.R = d.R; a.B = d.B; a.S = d.S;
-  a.KSW = prune_fast_ksw(d.V, d.M);
+  a.KSW = prune_fast_ksw(d);
+  if (const char* e = getenv("VNM_PRUNE_KSW")) { const int k = atoi(e); if (k >= 1 && k <= 8) a.KSW = k < a.KSW ? k : a.KSW; }
   const int chunks = a.KSW * d.M;
   a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
   a.values = (unsigned short*)values; a.meta = (unsigned char*)meta; a.colidx = (unsigned char*)colidx;
@@ -249,7 +265,7 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
     char* p = (char*)packed;
     a.pa = (uint4*)(p + pl.pa_off); a.pidx = (unsigned short*)(p + pl.pidx_off); a.pcol = (unsigned*)(p + pl.pcol_off);
   }
-  const size_t lds = prune_fast_lds(d.V, d.M, a.KSW, a.G, mask != nullptr);
+  const size_t lds = prune_fast_lds(d.V, d.M, a.KSW);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)prune_pack_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -266,66 +282,105 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
 }
 
 // ---------------------------------------------------------------- decompress
-// One workgroup: V rows x a span of column blocks.  The dense tile is assembled in LDS (zero fill,
-// then two 2-byte scatters per (row, block)) and written out with 16-byte stores.
-__global__ void __launch_bounds__(256)
-decompress_fast_kernel(const unsigned short* __restrict__ values, const unsigned char* __restrict__ meta,
-                       const unsigned char* __restrict__ colidx, int64_t out, int64_t in, int V, int M,
-                       int64_t B, int NBW, unsigned short* __restrict__ Wd, int64_t ldw) {
+// One workgroup: V rows x KSW K steps (8 KSW column blocks).  The dense tile is assembled in LDS
+// (zero fill, then two 2-byte scatters per (row, block), a thread taking 4 blocks of a row with one
+// 16-byte load of values and one 2-byte load of metadata) and written out with 16-byte stores.
+struct DecompArgs {
+  const unsigned short* values; const unsigned char* meta; const unsigned char* colidx;
+  int64_t out, in, B, S; int V, M, KSW, G;
+  unsigned short* Wd; int64_t ldw;
+};
+
+__global__ void __launch_bounds__(256) decompress_fast_kernel(const DecompArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int64_t r = blockIdx.y;
-  const int64_t b0 = (int64_t)blockIdx.x * NBW;
-  const int nb = (int)((B - b0) < NBW ? (B - b0) : NBW);
-  const int NCmax = NBW * M;                      // multiple of 8 (NBW is a multiple of 8)
-  const int NCP = NCmax + 8;
-  const int64_t c0 = b0 * M;
+  const int V = a.V, M = a.M;
+  const int64_t r = blockIdx.x;
+  const int64_t s_begin = (int64_t)blockIdx.y * a.KSW;
+  const int nks = (int)((a.S - s_begin) < a.KSW ? (a.S - s_begin) : a.KSW);
+  const int NC = a.KSW * 8 * M, NBW = a.KSW * 8;
+  const int NCP = NC + 8;
+  const int64_t b0 = s_begin * 8, c0 = b0 * M;
+  const int nbw = (int)((a.B - b0) < nks * 8 ? (a.B - b0) : nks * 8);
   unsigned short* tile = (unsigned short*)smem;
+  unsigned* keep = (unsigned*)(smem + (size_t)V * NCP * 2);
   const int tid = threadIdx.x;
-  const int chunks = NCmax / 8;
-  for (int item = tid; item < V * chunks; item += 256) {
-    const int v = item / chunks, ch = item - v * chunks;
-    *(uint4*)(tile + (size_t)v * NCP + ch * 8) = make_uint4(0, 0, 0, 0);
+  const int chunks = NC / 8, G = a.G;
+  const int g = tid / chunks, ch = tid - g * chunks;
+  if (g < G)
+    for (int v = g; v < V; v += G) *(uint4*)(tile + (size_t)v * NCP + ch * 8) = make_uint4(0, 0, 0, 0);
+  for (int b = tid; b < nbw; b += 256) keep[b] = *(const unsigned*)(a.colidx + (r * a.B + b0 + b) * 4);
+  __syncthreads();
+  {
+    const int64_t vrow_elems = 2 * a.B, mrow = (a.B + 1) / 2;
+    const bool v16 = (a.B & 3) == 0 && ((uintptr_t)a.values & 15) == 0;
+    const int nq = nks * 2;
+    const unsigned nq_inv = (65536u + nq - 1) / nq;
+    for (int item = tid; item < V * nq; item += 256) {
+      const int v = (int)(((unsigned)item * nq_inv) >> 16), qd = item - v * nq;   // item < 2^12, nq <= 16: exact
+      const int blk0 = qd * 4;
+      const int64_t row = r * V + v;
+      if (blk0 >= nbw || row >= a.out) continue;
+      const unsigned short* vsrc = a.values + row * vrow_elems + 2 * (b0 + blk0);
+      const unsigned char* msrc = a.meta + row * mrow + ((b0 + blk0) >> 1);
+      unsigned q[4] = {0, 0, 0, 0}, ix;
+      if (blk0 + 4 <= nbw) {
+        if (v16) { const uint4 t = *(const uint4*)vsrc; q[0] = t.x; q[1] = t.y; q[2] = t.z; q[3] = t.w; }
+        else { for (int e = 0; e < 4; ++e) q[e] = *(const unsigned*)(vsrc + 2 * e); }
+        unsigned short two;
+        __builtin_memcpy(&two, msrc, 2);
+        ix = two;
+      } else {
+        for (int e = 0; e < 4; ++e) if (blk0 + e < nbw) q[e] = *(const unsigned*)(vsrc + 2 * e);
+        ix = msrc[0];
+        if (blk0 + 2 < nbw) ix |= (unsigned)msrc[1] << 8;
+      }
+      unsigned short* trow = tile + (size_t)v * NCP + blk0 * M;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (blk0 + e < nbw) {
+          const unsigned nib = (ix >> (4 * e)) & 15u, kp = keep[blk0 + e];
+          const unsigned ca = min((kp >> (8 * (nib & 3))) & 255u, (unsigned)M - 1u);
+          const unsigned cb = min((kp >> (8 * (nib >> 2))) & 255u, (unsigned)M - 1u);
+          trow[e * M + ca] = (unsigned short)(q[e] & 0xFFFFu);
+          trow[e * M + cb] = (unsigned short)(q[e] >> 16);
+        }
+      }
+    }
   }
   __syncthreads();
-  for (int idx = tid; idx < V * nb; idx += 256) {
-    const int v = idx / nb, b = idx - v * nb;
-    const int64_t row = r * V + v;
-    if (row >= out) continue;
-    const uchar4 k4 = *(const uchar4*)(colidx + (r * B + b0 + b) * 4);
-    const unsigned char k[4] = {k4.x, k4.y, k4.z, k4.w};
-    const unsigned byte = meta[row * ((B + 1) / 2) + ((b0 + b) >> 1)];
-    const unsigned nib = ((b0 + b) & 1) ? (byte >> 4) : (byte & 15u);
-    const unsigned pair = *(const unsigned*)(values + row * 2 * B + 2 * (b0 + b));
-    unsigned short* trow = tile + (size_t)v * NCP + b * M;
-    trow[k[nib & 3]] = (unsigned short)(pair & 0xFFFFu);
-    trow[k[nib >> 2]] = (unsigned short)(pair >> 16);
-  }
-  __syncthreads();
-  for (int item = tid; item < V * chunks; item += 256) {
-    const int v = item / chunks, ch = item - v * chunks;
-    const int64_t row = r * V + v, col = c0 + ch * 8;
-    if (row < out && col < in) *(uint4*)(Wd + row * ldw + col) = *(const uint4*)(tile + (size_t)v * NCP + ch * 8);
+  if (g < G) {
+    const int64_t col = c0 + ch * 8;
+    if (col < a.in)
+      for (int v = g; v < V; v += G) {
+        const int64_t row = r * V + v;
+        if (row < a.out) *(uint4*)(a.Wd + row * a.ldw + col) = *(const uint4*)(tile + (size_t)v * NCP + ch * 8);
+      }
   }
 }
 
 bool decompress_fast_applicable(const void* W_out, int64_t ldw, const Dims& d) {
-  return d.M <= 16 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W_out & 15) == 0 && d.R <= 65535;
+  return d.M <= 16 && d.V <= 128 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W_out & 15) == 0 && d.S <= 65535;
 }
 
 int launch_decompress_fast(const void* values, const void* meta, const void* colidx, const Dims& d,
                            void* W_out, int64_t ldw, hipStream_t st) {
-  const int NBW = 8 * (128 / (8 * d.M) > 0 ? 128 / (8 * d.M) : 1);
-  const size_t lds = (size_t)d.V * (NBW * d.M + 8) * 2;
+  DecompArgs a;
+  a.values = (const unsigned short*)values; a.meta = (const unsigned char*)meta; a.colidx = (const unsigned char*)colidx;
+  a.out = d.out; a.in = d.in; a.B = d.B; a.S = d.S; a.V = d.V; a.M = d.M;
+  a.KSW = prune_fast_ksw(d);
+  if (const char* e = getenv("VNM_DECOMP_KSW")) { const int k = atoi(e); if (k >= 1 && k <= 8) a.KSW = k < a.KSW ? k : a.KSW; }
+  const int chunks = a.KSW * d.M;
+  a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
+  a.Wd = (unsigned short*)W_out; a.ldw = ldw;
+  const size_t lds = (size_t)d.V * (a.KSW * 8 * d.M + 8) * 2 + (size_t)a.KSW * 8 * 4;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)decompress_fast_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(decompress_fast)"); return VNM_ERR_HIP; }
     attr_set = true;
   }
-  dim3 grid((unsigned)((d.B + NBW - 1) / NBW), (unsigned)d.R);
-  hipLaunchKernelGGL(decompress_fast_kernel, grid, dim3(256), lds, st, (const unsigned short*)values,
-                     (const unsigned char*)meta, (const unsigned char*)colidx, d.out, d.in, d.V, d.M, d.B,
-                     NBW, (unsigned short*)W_out, ldw);
+  dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
+  hipLaunchKernelGGL(decompress_fast_kernel, grid, dim3(256), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "decompress_fast_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

@@ -44,7 +44,8 @@ inline PackedLayout packed_layout(const Dims& d) {
   p.pa_off = 0;
   p.pidx_off = up(d.R * d.S * tiles * 64 * 8 * 2);
   p.pcol_off = p.pidx_off + up(d.R * d.S * 64 * tiles * 2);
-  p.total = p.pcol_off + up(d.R * d.S * 32);
+  // + 8 KiB that the product kernel's look-ahead loads may read (never use) past the last row block
+  p.total = p.pcol_off + up(d.R * d.S * 32) + 8192;
   return p;
 }
 

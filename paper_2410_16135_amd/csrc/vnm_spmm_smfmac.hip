@@ -361,8 +361,12 @@ spmm_smfmac_kernel(const SpmmArgs a) {
 
   int64_t s = 0;
   if constexpr (kAsmLoop) {
-    // steady state: steps 0 .. S-NBUF (every step issues a copy NBUF-1 ahead and an A load 2 ahead)
-    if (S > NBUF - 1 && S > 3) {
+    // All S steps run in the assembly loop.  Every step requests the image NBUF-1 steps ahead and
+    // the A operand 2 steps ahead without looking at S: near the end these requests reach past the
+    // tile's images and past the row block's operands, into the next tile / row block or into the
+    // slack that the staged buffer (3 images) and the packed weight (8 KiB) carry for this
+    // purpose; what they fetch is never used.
+    {
       const uint64_t pa_p = (uint64_t)(a.pa + rr * S * AT * 64);
       const uint64_t pi_p = (uint64_t)(a.pidx + rr * S * 64 * AT);
       const uint64_t pc_p = (uint64_t)(a.pcol + rr * S * 8);
@@ -375,8 +379,7 @@ spmm_smfmac_kernel(const SpmmArgs a) {
       unsigned l_woff = wave * 1024, l_clamp = (n_ci - 1) * 1024, l_pitch = P, l_img = img;
       unsigned l_lbeg = __builtin_amdgcn_readfirstlane(lds0), l_lend = l_lbeg + NBUF * img;
       unsigned l_rd = l_lbeg, l_wr = l_lbeg + (NBUF - 1) * img, l_tci;
-      // steps with s + NBUF - 1 < S and s + 2 < S
-      const int64_t n_steady = (S - (NBUF - 1)) < (S - 2) ? (S - (NBUF - 1)) : (S - 2);
+      const int64_t n_steady = S;
       unsigned l_n = (unsigned)n_steady;
       // VMW = operations that may stay in flight at a step's wait: the 4 loads of A(s+2) issued at
       // its start and, with a ring of 4, the NCW copies issued after the previous step's barrier

@@ -59,7 +59,8 @@ stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int
 
 int64_t staged_bytes(int64_t T, const Dims& d) {
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
-  return tiles * d.S * image_bytes(d.M);
+  // + 3 images that the product kernel's look-ahead copies may read (never use) past the last tile
+  return (tiles * d.S + 3) * image_bytes(d.M);
 }
 
 int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st) {

@@ -11,49 +11,83 @@
 // per element per group of row blocks -- is what keeps the product kernel's inner loop free of
 // shuffles and of scattered 16-byte loads.
 #include "vnm_internal.h"
+#include <cstdlib>
 
 namespace vnm {
 
-// One workgroup: 128 tokens x (KG K steps).  Phase 1 reads rows of X with 16-byte loads (lanes along
-// the columns) into an LDS tile [token][column]; phase 2 reads it back column-wise and writes 16
-// bytes (8 tokens of one column) per lane, 16 lanes per image row.
-constexpr int kStageKG = 4;
-
+// One workgroup: one token tile x a run of sub-chunks of kStageKC K steps each.  Per sub-chunk,
+// rows of X are read with 16-byte loads (lanes along the columns) and parked in an LDS tile
+// [token][column]; the tile is read back column-wise and written 16 bytes (8 tokens of one column)
+// per lane, 16 lanes per image row.  The loads of the next sub-chunk are issued before the stores
+// of the current one, so that reads and writes of HBM overlap inside every workgroup.
+template <int kStageKC>
 __global__ void __launch_bounds__(256)
 stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int64_t in, int M,
-               int64_t S, int64_t image_bytes, unsigned char* __restrict__ Xs) {
+               int64_t S, int64_t image_bytes, int n_sub, unsigned char* __restrict__ Xs) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int64_t tile = blockIdx.x;
-  const int64_t s_begin = (int64_t)blockIdx.y * kStageKG;
-  const int nks = (int)((S - s_begin) < kStageKG ? (S - s_begin) : kStageKG);
-  const int ncol = nks * 8 * M;                 // columns of this workgroup (multiple of 8)
-  const int64_t col0 = s_begin * 8 * M;
+  const int64_t sub0 = (int64_t)blockIdx.y * n_sub;
   const int64_t t0 = tile * kTokTile;
-  const int pitch = ncol * 2 + 4;               // bytes; 4-byte aligned, odd number of dwords
+  const int CH = kStageKC * M;                         // 16-byte chunks per token row and sub-chunk
+  const int pitch = CH * 16 + 4;                       // bytes; odd number of dwords
   const int tid = threadIdx.x;
-  // phase 1
-  const int chunks = ncol / 8;                  // 16-byte chunks per token row
-  for (int item = tid; item < kTokTile * chunks; item += 256) {
-    const int tok = item / chunks, ch = item - tok * chunks;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (t0 + tok < T && col0 + ch * 8 < in) v = *(const uint4*)(X + (t0 + tok) * ldx + col0 + ch * 8);
-    unsigned* d = (unsigned*)(smem + (size_t)tok * pitch + ch * 16);
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-  }
-  __syncthreads();
-  // phase 2: item = (column c, token octet tq)
-  for (int item = tid; item < ncol * 16; item += 256) {
-    const int tq = item & 15, c = item >> 4;
-    const unsigned char* src = smem + (size_t)(tq * 8) * pitch + c * 2;
-    unsigned short h[8];
+  // item i of this thread is (token, chunk) number tid + 256 i in row-major order: NI items each
+  const int NI = kStageKC * M / 2;
+  const int tok_first = tid / CH, ch_first = tid - tok_first * CH;
+  const int dtok = 256 / CH, dch = 256 - dtok * CH;
+  uint4 w[16];
+  auto load = [&](int64_t sub) {
+    const int64_t col0 = sub * kStageKC * 8 * M;
+    int tok = tok_first, ch = ch_first;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) h[i] = *(const unsigned short*)(src + (size_t)i * pitch);
-    uint4 o;
-    o.x = h[0] | ((unsigned)h[1] << 16); o.y = h[2] | ((unsigned)h[3] << 16);
-    o.z = h[4] | ((unsigned)h[5] << 16); o.w = h[6] | ((unsigned)h[7] << 16);
-    const int ks = c / (8 * M), cr = c - ks * 8 * M;
-    unsigned char* dst = Xs + (tile * S + s_begin + ks) * image_bytes + (size_t)cr * kImagePitch + tq * 16;
-    *(uint4*)dst = o;
+    for (int i = 0; i < 16; ++i) {
+      if (i < NI) {
+        w[i] = make_uint4(0, 0, 0, 0);
+        if (t0 + tok < T && col0 + ch * 8 < in) w[i] = *(const uint4*)(X + (t0 + tok) * ldx + col0 + ch * 8);
+        ch += dch; tok += dtok;
+        if (ch >= CH) { ch -= CH; ++tok; }
+      }
+    }
+  };
+  if (sub0 * kStageKC < S) load(sub0);
+  for (int k = 0; k < n_sub; ++k) {
+    const int64_t sub = sub0 + k;
+    const int64_t s_begin = sub * kStageKC;
+    if (s_begin >= S) break;
+    {
+      int tok = tok_first, ch = ch_first;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (i < NI) {
+          unsigned* d = (unsigned*)(smem + (size_t)tok * pitch + ch * 16);
+          d[0] = w[i].x; d[1] = w[i].y; d[2] = w[i].z; d[3] = w[i].w;
+          ch += dch; tok += dtok;
+          if (ch >= CH) { ch -= CH; ++tok; }
+        }
+      }
+    }
+    __syncthreads();
+    if (k + 1 < n_sub && (sub + 1) * kStageKC < S) load(sub + 1);
+    // item = (column c, token octet tq)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (i < NI) {
+        const int tq = tid & 15, c = (tid >> 4) + 16 * i;
+        const int ks = kStageKC == 2 ? (c >= 8 * M ? 1 : 0) : c / (8 * M), cr = c - ks * 8 * M;
+        if (s_begin + ks < S) {
+          const unsigned char* src = smem + (size_t)(tq * 8) * pitch + c * 2;
+          unsigned short h[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) h[e] = *(const unsigned short*)(src + (size_t)e * pitch);
+          uint4 o;
+          o.x = h[0] | ((unsigned)h[1] << 16); o.y = h[2] | ((unsigned)h[3] << 16);
+          o.z = h[4] | ((unsigned)h[5] << 16); o.w = h[6] | ((unsigned)h[7] << 16);
+          unsigned char* dst = Xs + (tile * S + s_begin + ks) * image_bytes + (size_t)cr * kImagePitch + tq * 16;
+          *(uint4*)dst = o;
+        }
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -65,17 +99,31 @@ int64_t staged_bytes(int64_t T, const Dims& d) {
 
 int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st) {
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
-  if (tiles > 0x7FFFFFFF || (d.S + kStageKG - 1) / kStageKG > 65535) return VNM_ERR_UNSUPPORTED;
-  const size_t lds = (size_t)kTokTile * (kStageKG * 8 * d.M * 2 + 4);
+  // K steps per sub-chunk: 4 (rows of 64 M bytes per load) while a thread's share fits 16 registers sets
+  const int KC = d.M <= 8 ? 4 : 2;
+  const int64_t subs = (d.S + KC - 1) / KC;
+  // two sub-chunks per workgroup (one level of read/write overlap measured best) unless that
+  // would leave fewer workgroups than CUs
+  int64_t n_sub = tiles * subs >= 512 ? 2 : 1;
+  if (const char* e = getenv("VNM_STAGE_NSUB")) { const int k = atoi(e); if (k >= 1 && k <= 64) n_sub = k; }
+  const int64_t gy = (subs + n_sub - 1) / n_sub;
+  if (tiles > 0x7FFFFFFF || gy > 65535) return VNM_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)kTokTile * (KC * d.M * 16 + 4);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)stage_x_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(stage_x)"); return VNM_ERR_HIP; }
+    for (const void* f : {(const void*)stage_x_kernel<2>, (const void*)stage_x_kernel<4>}) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(stage_x)"); return VNM_ERR_HIP; }
+    }
     attr_set = true;
   }
-  dim3 grid((unsigned)tiles, (unsigned)((d.S + kStageKG - 1) / kStageKG));
-  hipLaunchKernelGGL(stage_x_kernel, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,
-                     d.S, image_bytes(d.M), (unsigned char*)Xs);
+  dim3 grid((unsigned)tiles, (unsigned)gy);
+  if (KC == 4)
+    hipLaunchKernelGGL(stage_x_kernel<4>, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,
+                       d.S, image_bytes(d.M), (int)n_sub, (unsigned char*)Xs);
+  else
+    hipLaunchKernelGGL(stage_x_kernel<2>, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,
+                       d.S, image_bytes(d.M), (int)n_sub, (unsigned char*)Xs);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "stage_x_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

@@ -214,7 +214,7 @@ def main():
     # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled by the calibration
     # copy); known only for the default workload
     default_wl = (args.workload == "llama2_7b" and L0_is_default(layers))
-    traffic = 342.0e6 if default_wl else None
+    traffic = 347.7e6 if default_wl else None
     dense_total = sum(dense_ms[L.name] for L in layers)
     L0 = layers[0]
     result = {

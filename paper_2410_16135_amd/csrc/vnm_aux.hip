@@ -49,9 +49,11 @@ int launch_decompress(const void* values, const void* meta, const void* colidx, 
 // last real one get value 0 and positions (0, 1).
 __global__ void __launch_bounds__(256)
 pack_kernel(const unsigned short* __restrict__ values, const unsigned char* __restrict__ meta,
-            const unsigned char* __restrict__ colidx, int V, int M, int64_t R, int64_t B, int64_t S,
+            const unsigned char* __restrict__ colidx, int V, int SB, int M, int64_t R, int64_t B, int64_t S,
             unsigned short* __restrict__ pa, unsigned short* __restrict__ pidx,
             unsigned char* __restrict__ pcol) {
+  // R, V here are those of the packed copy (row blocks of VP = packed_v(V) rows); SB of them share
+  // one row block of the pattern and its column indices
   const int tiles = V / 32;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t total = R * S * tiles * 64;
@@ -96,7 +98,7 @@ pack_kernel(const unsigned short* __restrict__ values, const unsigned char* __re
     for (int m = 0; m < 4; ++m) {
       const int blk = 4 * (m >> 1) + 2 * h + (m & 1);
       const int64_t b = s * 8 + blk;
-      const unsigned c = (b < B) ? colidx[(r * B + b) * 4 + kq] : (unsigned)kq;
+      const unsigned c = (b < B) ? colidx[((r / SB) * B + b) * 4 + kq] : (unsigned)kq;
       o |= (unsigned)(blk * M + c) << (8 * m);
     }
     *(unsigned*)(pcol + gid * 4) = o;
@@ -107,11 +109,12 @@ int launch_pack(const void* values, const void* meta, const void* colidx, const 
                 void* packed, hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   if (pl.total == 0) return VNM_ERR_UNSUPPORTED;
-  const int64_t total = d.R * d.S * (d.V / 32) * 64;
+  const int VP = packed_v(d.V), SB = d.V / VP;
+  const int64_t total = d.R * SB * d.S * (VP / 32) * 64;
   char* p = (char*)packed;
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                      (const unsigned short*)values, (const unsigned char*)meta,
-                     (const unsigned char*)colidx, d.V, d.M, d.R, d.B, d.S,
+                     (const unsigned char*)colidx, VP, SB, d.M, d.R * SB, d.B, d.S,
                      (unsigned short*)(p + pl.pa_off), (unsigned short*)(p + pl.pidx_off),
                      (unsigned char*)(p + pl.pcol_off));
   hipError_t e = hipGetLastError();

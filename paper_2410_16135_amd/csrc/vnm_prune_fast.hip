@@ -128,13 +128,14 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   // [2e+1 : 2e].  The matrix-core copy is stored from here; the canonical values and metadata of
   // the four blocks are parked in the tile, over the 4M elements they came from, for phase 3.
   const int tiles = V / 32;
+  const int ptiles = tiles > 2 ? 2 : tiles;          // 32-row tiles per packed row block
+  const int SB = tiles / ptiles;                     // packed row blocks per row block of the pattern
   for (int item = tid; item < nks * 64; item += 256) {
     const int ks = item >> 6, lane = item & 63;
     const int i = lane & 31, h = lane >> 5;
     const int blk0 = ks * 8 + 4 * h;
     const uint4 kp4 = *(const uint4*)(keep + blk0);
     const unsigned kp[4] = {kp4.x, kp4.y, kp4.z, kp4.w};
-    const int64_t rs = r * a.S + s_begin + ks;
     unsigned short ixs[4] = {0, 0, 0, 0};
     for (int at = 0; at < tiles; ++at) {
       const int v = at * 32 + i;
@@ -149,17 +150,22 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         ix |= nib << (4 * g);
       }
       ixs[at] = (unsigned short)ix;
-      if (a.pa) a.pa[(rs * tiles + at) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
+      if (a.pa) {
+        // packed row block (at most 64 rows) and 32-row tile inside it
+        const int64_t rp = r * SB + at / ptiles;
+        a.pa[(((rp * a.S + s_begin + ks) * ptiles) + at % ptiles) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
+      }
       // 8-byte aligned: blk0 is a multiple of 4
       *(uint2*)trow = make_uint2(q[0], q[1]);
       *(uint2*)(trow + 4) = make_uint2(q[2], q[3]);
       trow[8] = (unsigned short)ix;
     }
     if (a.pa) {
-      unsigned short* pd = a.pidx + (rs * 64 + lane) * tiles;
-      if (tiles == 1) pd[0] = ixs[0];
-      else if (tiles == 2) *(unsigned*)pd = (unsigned)ixs[0] | ((unsigned)ixs[1] << 16);
-      else *(uint2*)pd = make_uint2((unsigned)ixs[0] | ((unsigned)ixs[1] << 16), (unsigned)ixs[2] | ((unsigned)ixs[3] << 16));
+      if (ptiles == 1) a.pidx[(r * a.S + s_begin + ks) * 64 + lane] = ixs[0];
+      else
+        for (int sb = 0; sb < SB; ++sb)
+          *(unsigned*)(a.pidx + (((r * SB + sb) * a.S + s_begin + ks) * 64 + lane) * 2) =
+              (unsigned)ixs[2 * sb] | ((unsigned)ixs[2 * sb + 1] << 16);
     }
   }
   __syncthreads();
@@ -207,7 +213,7 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         const unsigned c = (keep[ks * 8 + blk] >> (8 * kq)) & 255u;
         o |= (unsigned)(blk * M + c) << (8 * m);
       }
-      a.pcol[(r * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
+      for (int sb = 0; sb < SB; ++sb) a.pcol[((r * SB + sb) * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
     }
   }
   // phase 4: optional dense 0-1 mask, from the positions parked in the tile

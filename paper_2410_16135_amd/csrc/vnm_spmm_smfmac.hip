@@ -534,24 +534,24 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.pa = (const uint4*)(p + pl.pa_off);
   a.pidx = (const unsigned short*)(p + pl.pidx_off);
   a.pcol = (const unsigned*)(p + pl.pcol_off);
-  a.out = d.out; a.R = d.R; a.S = d.S; a.M = d.M;
+  const int VP = packed_v(d.V);
+  a.out = d.out; a.R = d.R * (d.V / VP); a.S = d.S; a.M = d.M;     // row blocks of the packed copy
   a.image_bytes = (int)image_bytes(d.M);
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.wide_store = (y_dtype == 0) && (ldy % 8 == 0) && (((uintptr_t)Y & 15) == 0);
   a.vec_store = (ldy % 4 == 0) && (((uintptr_t)Y & (y_dtype == 0 ? 7 : 15)) == 0);
-  if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (d.R + 1) / 2 > 65535) return VNM_ERR_UNSUPPORTED;
+  if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (a.R + 1) / 2 > 65535) return VNM_ERR_UNSUPPORTED;
   const bool deep = 2 * 4 * (size_t)a.image_bytes <= 150 * 1024;
   // 8 row blocks per workgroup halve the image traffic per flop; worth it when there are enough
   // row blocks to keep every CU busy with one such workgroup
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
-  bool wide = d.R >= 8 && tiles * ((d.R + 7) / 8) >= 200;
+  bool wide = a.R >= 8 && tiles * ((a.R + 7) / 8) >= 200;
   { const char* e = getenv("VNM_SPMM_WG"); if (e) wide = atoi(e) == 8; }
-  switch (d.V) {
+  switch (VP) {
     case 32: return launch_cfg<32, 128, 8, 1, 0, 3>(a, st);
     case 64:
       if (wide) return 4 * (size_t)a.image_bytes <= 150 * 1024 ? launch_v64_w8<4>(a, st) : launch_v64_w8<3>(a, st);
       return deep ? launch_v64_w4<4>(a, st) : launch_v64_w4<3>(a, st);
-    case 128: return launch_cfg<128, 64, 2, 2, 0, 3>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }

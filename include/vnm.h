@@ -103,9 +103,11 @@ int vnm_pack(const void* values, const void* meta, const void* colidx,
  *   Y        dev [T x out], leading dimension ldy >= out; y_dtype 0 = fp16, 1 = fp32
  *   packed   dev or NULL (NULL forces the generic kernel under VNM_PATH_AUTO)
  *   path     a vnm_spmm_path
- *   workspace  dev, 256-byte aligned, at least vnm_spmm_workspace_bytes(T, ...) bytes: the
- *            matrix-core kernel first re-lays X there (token tiles x K steps, column-major inside,
- *            the order it streams through LDS); contents are scratch, nothing persists
+ *   workspace  dev, 256-byte aligned, vnm_spmm_workspace_bytes(T, ...) bytes: the matrix-core
+ *            kernel first re-lays X there (token tiles x K steps, column-major inside, the order
+ *            it streams through LDS; vnm_stage_x_bytes bytes, the required minimum); the rest
+ *            (vnm_spmm_scratch_bytes, optional) holds fp32 partial products when, for few tokens,
+ *            the K dimension is split over workgroups; contents are scratch, nothing persists
  * The matrix-core kernel needs V in {32, 64, 128}, M <= 16, in % 8 == 0, ldx % 8 == 0 and X 16-byte
  * aligned; otherwise (or when `packed` is NULL) AUTO uses the generic kernel, which needs no
  * workspace.  When the matrix-core kernel applies but the workspace is missing or too small the
@@ -122,18 +124,24 @@ int vnm_spmm(const void* X, int64_t T, int64_t ldx,
  * The two halves of vnm_spmm's matrix-core path as separate calls, for callers that feed the same
  * activations to several layers (the q/k/v projections or the gate/up projections of a block share
  * their input): re-lay X once, multiply many times.  Same arguments and errors as vnm_spmm;
- * `staged` is the workspace described there (vnm_spmm_workspace_bytes bytes, 256-byte aligned) and
- * depends only on T, in and M, not on the layer's weights.  vnm_spmm_staged fails with
+ * `staged` (vnm_stage_x_bytes(T, in, M) bytes, 256-byte aligned) holds the re-laid activations and
+ * depends only on T, in and M, not on the layer's weights.  `scratch` (vnm_spmm_scratch_bytes(T, out)
+ * bytes, 256-byte aligned, or NULL) is the optional split-K scratch: without it, or with less than
+ * asked for, the product is still correct, only slower for small T.  vnm_spmm_staged fails with
  * VNM_ERR_UNSUPPORTED where vnm_spmm would have used the generic kernel.
  */
 int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, int M,
                 void* staged, int64_t staged_bytes, void* stream);
 int vnm_spmm_staged(const void* staged, int64_t T, const void* packed,
                     int64_t out, int64_t in, int V, int N, int M,
-                    void* Y, int64_t ldy, int y_dtype, void* stream);
+                    void* Y, int64_t ldy, int y_dtype,
+                    void* scratch, int64_t scratch_bytes, void* stream);
+/* Host only.  Sizes of the two buffers above. */
+int vnm_stage_x_bytes(int64_t T, int64_t in, int M, int64_t* bytes);
+int vnm_spmm_scratch_bytes(int64_t T, int64_t out, int64_t* bytes);
 
-/* Host only.  Bytes of workspace vnm_spmm needs for T tokens of this layer (0 if the matrix-core
- * kernel does not exist for this V, M). */
+/* Host only.  Bytes of workspace vnm_spmm wants for T tokens of this layer: staged activations
+ * (rounded up to 256) + split-K scratch (0 if the matrix-core kernel does not exist for this V, M). */
 int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M, int64_t* bytes);
 
 /* Inverse of the conversion of Appendix A: dense fp16 W' [out x in] (leading dimension ldw),

@@ -46,11 +46,15 @@ def load_library():
     lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
     lib.vnm_stage_x.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
-    lib.vnm_spmm_staged.argtypes = [vp, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp]
+    lib.vnm_spmm_staged.argtypes = [vp, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, i64, vp]
     lib.vnm_stage_x.restype = ci
     lib.vnm_spmm_staged.restype = ci
     lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_workspace_bytes.restype = ci
+    lib.vnm_stage_x_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(i64)]
+    lib.vnm_stage_x_bytes.restype = ci
+    lib.vnm_spmm_scratch_bytes.argtypes = [i64, i64, ctypes.POINTER(i64)]
+    lib.vnm_spmm_scratch_bytes.restype = ci
     for f in (lib.vnm_query_sizes, lib.vnm_prune_compress, lib.vnm_pack, lib.vnm_spmm, lib.vnm_decompress,
               lib.vnm_format_version):
         f.restype = ci
@@ -153,7 +157,8 @@ def _workspace(device, nbytes: int):
     import torch
     ws = _WORKSPACES.get(device)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device)
+        dev = device[0] if isinstance(device, tuple) else device
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=dev)
         _WORKSPACES[device] = ws
     return ws
 
@@ -188,7 +193,7 @@ def vnm_stage_x(X, M: int, staged=None):
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
     T, inn = X.shape
     b = ctypes.c_int64(0)
-    _check(load_library().vnm_spmm_workspace_bytes(T, 64, inn, 64, 2, M, ctypes.byref(b)), "vnm_spmm_workspace_bytes")
+    _check(load_library().vnm_stage_x_bytes(T, inn, M, ctypes.byref(b)), "vnm_stage_x_bytes")
     if staged is None:
         staged = torch.empty(max(b.value, 1), dtype=torch.uint8, device=X.device)
     _check(load_library().vnm_stage_x(_ptr(X), T, X.stride(0) if T > 0 else inn, inn, M, _ptr(staged),
@@ -196,14 +201,27 @@ def vnm_stage_x(X, M: int, staged=None):
     return staged
 
 
-def vnm_spmm_staged(staged, T: int, c: Compressed, N: int = 2, out_dtype=None, Y=None):
-    """Y [T x out] from activations staged by vnm_stage_x and the packed weight of `c`."""
+def vnm_spmm_scratch_bytes(T: int, out: int) -> int:
+    b = ctypes.c_int64(0)
+    _check(load_library().vnm_spmm_scratch_bytes(T, out, ctypes.byref(b)), "vnm_spmm_scratch_bytes")
+    return b.value
+
+
+def vnm_spmm_staged(staged, T: int, c: Compressed, N: int = 2, out_dtype=None, Y=None, scratch=None):
+    """Y [T x out] from activations staged by vnm_stage_x and the packed weight of `c`.
+    `scratch`: optional uint8 CUDA tensor for the split-K partial products (small T); by default
+    the process-wide scratch tensor is used when vnm_spmm_scratch_bytes(T, out) > 0."""
     import torch
     if Y is None:
         Y = torch.empty((T, c.out), dtype=out_dtype or torch.float16, device=staged.device)
     y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    if scratch is None:
+        nb = vnm_spmm_scratch_bytes(T, c.out)
+        if nb > 0:
+            scratch = _workspace((staged.device, "splitk"), nb)
     _check(load_library().vnm_spmm_staged(_ptr(staged), T, _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y),
-                                          Y.stride(0) if T > 0 else c.out, y_dtype, _stream(staged)),
+                                          Y.stride(0) if T > 0 else c.out, y_dtype, _ptr(scratch),
+                                          scratch.numel() if scratch is not None else 0, _stream(staged)),
            "vnm_spmm_staged")
     return Y
 

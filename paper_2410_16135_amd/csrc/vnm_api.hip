@@ -101,7 +101,11 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
     if ((uintptr_t)workspace & 255) return VNM_ERR_ALIGN;
     rc = launch_stage_x(X, T, ldx, d, workspace, st);
     if (rc) return rc;
-    return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, st);
+    // whatever follows the staged activations serves as split-K scratch
+    const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
+    void* scratch = workspace_bytes > sb ? (char*)workspace + sb : nullptr;
+    return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, scratch,
+                              scratch ? workspace_bytes - sb : 0, st);
   }
   return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, st);
 }
@@ -121,7 +125,7 @@ extern "C" int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, in
 
 extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed, int64_t out,
                                int64_t in, int V, int N, int M, void* Y, int64_t ldy, int y_dtype,
-                               void* stream) {
+                               void* scratch, int64_t scratch_bytes, void* stream) {
   if (T != 0 && (!staged || !packed || !Y)) return VNM_ERR_NULL;
   int rc = check_pattern(out, in, V, N, M);
   if (rc) return rc;
@@ -130,9 +134,11 @@ extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed
   if (!has_packed(V, M) || in % 8 != 0) return VNM_ERR_UNSUPPORTED;
   if (((uintptr_t)staged & 255) || ((uintptr_t)packed & 255)) return VNM_ERR_ALIGN;
   if ((uintptr_t)Y & (y_dtype == 0 ? 1 : 3)) return VNM_ERR_ALIGN;
+  if (scratch_bytes < 0) return VNM_ERR_WORKSPACE;
+  if (scratch && ((uintptr_t)scratch & 255)) return VNM_ERR_ALIGN;
   if (T == 0) return VNM_OK;
-  return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype,
-                            (hipStream_t)stream);
+  return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype, scratch,
+                            scratch ? scratch_bytes : 0, (hipStream_t)stream);
 }
 
 extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
@@ -141,7 +147,22 @@ extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int 
   int rc = check_pattern(out, in, V, N, M);
   if (rc) return rc;
   if (T < 0) return VNM_ERR_SHAPE;
-  *bytes = has_packed(V, M) ? staged_bytes(T, make_dims(out, in, V, M)) : 0;
+  *bytes = has_packed(V, M) ? (staged_bytes(T, make_dims(out, in, V, M)) + 255) / 256 * 256 + splitk_scratch_bytes(T, out) : 0;
+  return VNM_OK;
+}
+
+extern "C" int vnm_stage_x_bytes(int64_t T, int64_t in, int M, int64_t* bytes) {
+  if (!bytes) return VNM_ERR_NULL;
+  if (in <= 0 || T < 0) return VNM_ERR_SHAPE;
+  if (M < 4 || M > 16) return VNM_ERR_UNSUPPORTED;
+  *bytes = staged_bytes(T, make_dims(64, in, 64, M));
+  return VNM_OK;
+}
+
+extern "C" int vnm_spmm_scratch_bytes(int64_t T, int64_t out, int64_t* bytes) {
+  if (!bytes) return VNM_ERR_NULL;
+  if (out <= 0 || T < 0) return VNM_ERR_SHAPE;
+  *bytes = splitk_scratch_bytes(T, out);
   return VNM_OK;
 }
 

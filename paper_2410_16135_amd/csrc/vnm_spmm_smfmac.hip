@@ -199,6 +199,7 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
       VNM_ASM_LOAD_A("224:227", "228:231", "232", "233")                                          \
       VNM_ASM_LOAD_A("234:237", "238:241", "242", "243")                                          \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
+      "s_barrier\n"                                                                               \
       VNM_ASM_ADDR("233")                                                                         \
       VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
       VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
@@ -238,6 +239,9 @@ struct SpmmArgs {
   int vec_store;     // Y and ldy allow 4-wide stores
   int wide_store;    // fp16 Y: 16-byte aligned base and ldy % 8 == 0 (LDS-transposed epilogue)
   int y_fp32;
+  // split K: workgroup z handles K steps [z * ks_steps, min(S, (z + 1) * ks_steps)) and writes its
+  // partial product to Y + z * z_stride elements (an fp32 scratch then, summed by a second kernel)
+  int64_t ks_steps, z_stride;
 };
 
 // One K step = 8 column blocks = 8*M raw input columns = 32 compacted K = one staged image.
@@ -261,7 +265,9 @@ spmm_smfmac_kernel(const SpmmArgs a) {
   const bool r_valid = r < a.R;
   const int64_t rr = r_valid ? r : a.R - 1;      // out-of-range waves compute a valid row block, store nothing
   const int64_t t0 = (int64_t)blockIdx.x * kTokTile;
-  const int64_t S = a.S;
+  const int64_t s0 = (int64_t)blockIdx.z * a.ks_steps;
+  const int64_t S = (a.S - s0) < a.ks_steps ? (a.S - s0) : a.ks_steps;   // steps of this workgroup
+  const int64_t rs0 = rr * a.S + s0;                                      // its first (row block, step)
   const int img = a.image_bytes;
   const int n_ci = img / 1024;                   // wave-wide copies per image
   const int ncw = (n_ci + NW - 1) / NW;          // copies per wave and image
@@ -279,7 +285,7 @@ spmm_smfmac_kernel(const SpmmArgs a) {
   const unsigned lds0 = (unsigned)(size_t)(VNM_LDS(unsigned char))smem;
   const unsigned tokoff = (unsigned)((wt * TW + tg * 16 + q * 4) * 2);
 
-  const unsigned char* xs_tile = a.Xs + (int64_t)blockIdx.x * S * img;
+  const unsigned char* xs_tile = a.Xs + ((int64_t)blockIdx.x * a.S + s0) * img;
   // copy this wave's share of image s into ring slot `slot`; chunks beyond the image are clamped to
   // its last chunk (an idempotent duplicate) so that every wave issues the same number of copies
   auto copy_image = [&](int64_t s, int slot) {
@@ -294,16 +300,16 @@ spmm_smfmac_kernel(const SpmmArgs a) {
 
   // A operand of one K step as it sits in registers
   struct AOp { uint4 w[AT]; unsigned idx[NI]; unsigned pc4; };
-  const uint4* pa_w = a.pa + rr * S * AT * 64 + lane;
+  const uint4* pa_w = a.pa + rs0 * AT * 64 + lane;
   const unsigned* pidx_w = (const unsigned*)a.pidx;      // AT >= 2: AT/2 dwords per lane and step
-  const unsigned* pcol_w = a.pcol + rr * S * 8 + hB * 4 + kq;
+  const unsigned* pcol_w = a.pcol + rs0 * 8 + hB * 4 + kq;
   auto load_a = [&](AOp& o, int64_t s) {
 #pragma unroll
     for (int i = 0; i < AT; ++i) o.w[i] = pa_w[(s * AT + i) * 64];
-    if (AT == 1) o.idx[0] = a.pidx[(rr * S + s) * 64 + lane];
+    if (AT == 1) o.idx[0] = a.pidx[(rs0 + s) * 64 + lane];
     else {
 #pragma unroll
-      for (int i = 0; i < AT / 2; ++i) o.idx[i] = pidx_w[((rr * S + s) * 64 + lane) * (AT / 2) + i];
+      for (int i = 0; i < AT / 2; ++i) o.idx[i] = pidx_w[((rs0 + s) * 64 + lane) * (AT / 2) + i];
     }
     o.pc4 = pcol_w[s * 8];
   };
@@ -354,10 +360,13 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     cur = nxt;
   };
 
-  // prologue: the first NBUF-1 images
+  // prologue: the first NBUF-1 images (the assembly loop waits for them together with its first
+  // A operands, one memory latency instead of two)
   for (int k = 0; k < NBUF - 1 && k < S; ++k) copy_image(k, k);
-  wait_vmcnt_imm<0>();
-  __builtin_amdgcn_s_barrier();
+  if constexpr (!kAsmLoop) {
+    wait_vmcnt_imm<0>();
+    __builtin_amdgcn_s_barrier();
+  }
 
   int64_t s = 0;
   if constexpr (kAsmLoop) {
@@ -367,9 +376,9 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     // slack that the staged buffer (3 images) and the packed weight (8 KiB) carry for this
     // purpose; what they fetch is never used.
     {
-      const uint64_t pa_p = (uint64_t)(a.pa + rr * S * AT * 64);
-      const uint64_t pi_p = (uint64_t)(a.pidx + rr * S * 64 * AT);
-      const uint64_t pc_p = (uint64_t)(a.pcol + rr * S * 8);
+      const uint64_t pa_p = (uint64_t)(a.pa + rs0 * AT * 64);
+      const uint64_t pi_p = (uint64_t)(a.pidx + rs0 * 64 * AT);
+      const uint64_t pc_p = (uint64_t)(a.pcol + rs0 * 8);
       const uint64_t xs_p = (uint64_t)(xs_tile + (int64_t)(NBUF - 1) * img);
       unsigned l_pa_lo = __builtin_amdgcn_readfirstlane((unsigned)pa_p), l_pa_hi = __builtin_amdgcn_readfirstlane((unsigned)(pa_p >> 32));
       unsigned l_pi_lo = __builtin_amdgcn_readfirstlane((unsigned)pi_p), l_pi_hi = __builtin_amdgcn_readfirstlane((unsigned)(pi_p >> 32));
@@ -423,7 +432,7 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     constexpr int LPT = V / 8;                            // lanes per token row (16 bytes each)
     constexpr int TPI = 64 / LPT;                         // token rows per wave-wide store
     const int ch = lane % LPT, tl = lane / LPT;
-    _Float16* Yh = (_Float16*)a.Y;
+    _Float16* Yh = (_Float16*)a.Y + (int64_t)blockIdx.z * a.z_stride;
 #pragma unroll
     for (int it = 0; it < TW / TPI; ++it) {
       const int tk = it * TPI + tl;
@@ -466,8 +475,8 @@ spmm_smfmac_kernel(const SpmmArgs a) {
         const int64_t o = r * V + i * 32 + 8 * jq + 4 * hB;
         const float v0 = acc[i][j][4 * jq], v1 = acc[i][j][4 * jq + 1], v2 = acc[i][j][4 * jq + 2],
                     v3 = acc[i][j][4 * jq + 3];
-        if (a.y_fp32) store4((float*)a.Y + tok * a.ldy + o, o, v0, v1, v2, v3);
-        else store4((_Float16*)a.Y + tok * a.ldy + o, o, v0, v1, v2, v3);
+        if (a.y_fp32) store4((float*)a.Y + (int64_t)blockIdx.z * a.z_stride + tok * a.ldy + o, o, v0, v1, v2, v3);
+        else store4((_Float16*)a.Y + (int64_t)blockIdx.z * a.z_stride + tok * a.ldy + o, o, v0, v1, v2, v3);
       }
     }
   }
@@ -489,7 +498,8 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
     if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(spmm_smfmac)"); return VNM_ERR_HIP; }
     attr_set = true;
   }
-  dim3 grid((unsigned)((a.T + kTokTile - 1) / kTokTile), (unsigned)((a.R + WR - 1) / WR));
+  dim3 grid((unsigned)((a.T + kTokTile - 1) / kTokTile), (unsigned)((a.R + WR - 1) / WR),
+            (unsigned)((a.S + a.ks_steps - 1) / a.ks_steps));
   hipLaunchKernelGGL(kern, grid, dim3(64 * WR * WT), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_smfmac_kernel"); return VNM_ERR_HIP; }
@@ -525,8 +535,39 @@ static int launch_v64_w8(const SpmmArgs& a, hipStream_t st) {
   return VNM_ERR_UNSUPPORTED;
 }
 
+// Sum of the KS fp32 partial products [KS][T][out] into Y (fp16 or fp32, leading dimension ldy).
+template <typename OutT>
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, int KS, int64_t T, int64_t out, OutT* __restrict__ Y, int64_t ldy) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= T * out) return;
+  float acc = 0.f;
+  const float* p = part + idx;
+  const int64_t zs = T * out;
+  int z = 0;
+  for (; z + 4 <= KS; z += 4) {
+    const float a0 = p[(int64_t)z * zs], a1 = p[(int64_t)(z + 1) * zs], a2 = p[(int64_t)(z + 2) * zs],
+                a3 = p[(int64_t)(z + 3) * zs];
+    acc += (a0 + a1) + (a2 + a3);
+  }
+  for (; z < KS; ++z) acc += p[(int64_t)z * zs];
+  const int64_t t = idx / out, o = idx - t * out;
+  Y[t * ldy + o] = (OutT)acc;
+}
+
+constexpr int64_t kSplitKMaxTokens = 256;
+constexpr int64_t kSplitKMaxBytes = 64ll << 20;
+
+int64_t splitk_scratch_bytes(int64_t T, int64_t out) {
+  if (T <= 0 || T > kSplitKMaxTokens) return 0;
+  int64_t b = 16 * T * out * 4;
+  if (b > kSplitKMaxBytes) b = kSplitKMaxBytes;
+  return (b + 255) / 256 * 256;
+}
+
 int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,
-                       void* Y, int64_t ldy, int y_dtype, hipStream_t st) {
+                       void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
+                       hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
   SpmmArgs a;
@@ -538,8 +579,7 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.out = d.out; a.R = d.R * (d.V / VP); a.S = d.S; a.M = d.M;     // row blocks of the packed copy
   a.image_bytes = (int)image_bytes(d.M);
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
-  a.wide_store = (y_dtype == 0) && (ldy % 8 == 0) && (((uintptr_t)Y & 15) == 0);
-  a.vec_store = (ldy % 4 == 0) && (((uintptr_t)Y & (y_dtype == 0 ? 7 : 15)) == 0);
+  a.ks_steps = d.S; a.z_stride = 0;
   if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (a.R + 1) / 2 > 65535) return VNM_ERR_UNSUPPORTED;
   const bool deep = 2 * 4 * (size_t)a.image_bytes <= 150 * 1024;
   // 8 row blocks per workgroup halve the image traffic per flop; worth it when there are enough
@@ -547,13 +587,47 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
   bool wide = a.R >= 8 && tiles * ((a.R + 7) / 8) >= 200;
   { const char* e = getenv("VNM_SPMM_WG"); if (e) wide = atoi(e) == 8; }
-  switch (VP) {
-    case 32: return launch_cfg<32, 128, 8, 1, 0, 3>(a, st);
-    case 64:
-      if (wide) return 4 * (size_t)a.image_bytes <= 150 * 1024 ? launch_v64_w8<4>(a, st) : launch_v64_w8<3>(a, st);
-      return deep ? launch_v64_w4<4>(a, st) : launch_v64_w4<3>(a, st);
+  // Few tokens: too few (token tile, row group) pairs to occupy the 256 CUs, and the job is to
+  // stream the compressed weight at HBM rate.  Split K over up to 16 workgroups per pair; each
+  // writes an fp32 partial product to the scratch, a second kernel adds them up.
+  int KS = 1;
+  const int64_t base = tiles * ((a.R + 3) / 4);
+  if (scratch && T <= kSplitKMaxTokens && base < 192 && VP == 64) {
+    int64_t ks = (200 + base / 2) / base;                            // about 200 workgroups measured best
+    if (ks > 16) ks = 16;
+    if (ks > d.S / 4) ks = d.S / 4;                                   // at least 4 K steps each
+    while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
+    if (const char* e = getenv("VNM_SPMM_KS")) { const int k = atoi(e); if (k >= 1 && k <= 16 && k <= d.S) ks = k; }
+    if (ks > 1) {
+      a.ks_steps = (d.S + ks - 1) / ks;
+      KS = (int)((d.S + a.ks_steps - 1) / a.ks_steps);
+    }
   }
-  return VNM_ERR_UNSUPPORTED;
+  if (KS > 1) {
+    a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
+    wide = false;
+  }
+  a.wide_store = (a.y_fp32 == 0) && (a.ldy % 8 == 0) && (((uintptr_t)a.Y & 15) == 0);
+  a.vec_store = (a.ldy % 4 == 0) && (((uintptr_t)a.Y & (a.y_fp32 == 0 ? 7 : 15)) == 0);
+  int rc = VNM_ERR_UNSUPPORTED;
+  switch (VP) {
+    case 32: rc = launch_cfg<32, 128, 8, 1, 0, 3>(a, st); break;
+    case 64:
+      if (wide) rc = 4 * (size_t)a.image_bytes <= 150 * 1024 ? launch_v64_w8<4>(a, st) : launch_v64_w8<3>(a, st);
+      else rc = deep ? launch_v64_w4<4>(a, st) : launch_v64_w4<3>(a, st);
+      break;
+  }
+  if (rc != VNM_OK || KS == 1) return rc;
+  const int64_t n = T * d.out;
+  if (y_dtype == 0)
+    hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       (const float*)scratch, KS, T, d.out, (_Float16*)Y, ldy);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       (const float*)scratch, KS, T, d.out, (float*)Y, ldy);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "splitk_reduce_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
 }
 
 }  // namespace vnm

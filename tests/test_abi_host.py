@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(vnm_[a-z_]+)\s*\(", text))
     assert {"vnm_query_sizes", "vnm_prune_compress", "vnm_pack", "vnm_spmm", "vnm_decompress", "vnm_stage_x",
-            "vnm_spmm_staged", "vnm_spmm_workspace_bytes",
+            "vnm_spmm_staged", "vnm_spmm_workspace_bytes", "vnm_stage_x_bytes", "vnm_spmm_scratch_bytes",
             "vnm_status_string", "vnm_last_hip_error", "vnm_format_version"} <= names
     for n in names:
         assert hasattr(lib, n), n
@@ -86,8 +86,18 @@ def test_argument_errors(lib):
     assert lib.vnm_stage_x(good, 4, 100, 128, 5, a256, 1 << 30, None) == 2          # ldx < in
     assert lib.vnm_stage_x(good, 4, 128, 128, 17, a256, 1 << 30, None) == 3         # M beyond the matrix-core range
     assert lib.vnm_stage_x(good, 4, 128, 128, 5, a256, 16, None) == 5
-    assert lib.vnm_spmm_staged(a256, 4, None, 128, 128, 64, 2, 8, good, 128, 0, None) == 1
-    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 16, 2, 8, good, 128, 0, None) == 3
+    assert lib.vnm_spmm_staged(a256, 4, None, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 1
+    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 16, 2, 8, good, 128, 0, None, 0, None) == 3
+    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, P(0x1008), 1 << 20, None) == 4   # scratch misaligned
+    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, a256, -1, None) == 5
+    # sizes: staged activations alone, split-K scratch (small token counts only), and their sum
+    sb, kb = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    assert lib.vnm_stage_x_bytes(4096, 4096, 5, ctypes.byref(sb)) == 0 and sb.value == (32 * 103 + 3) * 13312
+    assert lib.vnm_spmm_scratch_bytes(4096, 4096, ctypes.byref(kb)) == 0 and kb.value == 0
+    assert lib.vnm_spmm_scratch_bytes(16, 11008, ctypes.byref(kb)) == 0 and kb.value == 16 * 16 * 11008 * 4
+    assert lib.vnm_stage_x_bytes(16, 4096, 5, ctypes.byref(sb)) == 0 and sb.value == (103 + 3) * 13312
+    assert lib.vnm_spmm_workspace_bytes(16, 11008, 4096, 64, 2, 5, ctypes.byref(b)) == 0 and b.value == sb.value + kb.value
+    assert lib.vnm_stage_x_bytes(16, 4096, 17, ctypes.byref(sb)) == 3
     assert lib.vnm_status_string(0) == b"ok" and b"null" in lib.vnm_status_string(1)
 
 

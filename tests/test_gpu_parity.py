@@ -178,6 +178,40 @@ def test_stage_once_multiply_many():
         assert orc.max_normalised_error(Y1.cpu().numpy(), Y_ref) <= TOL
 
 
+SPLITK_CASES = [
+    # out, in, T, V, M: few tokens, enough K steps (in / 8M) for the product to be split along K
+    (1024, 4096, 16, 64, 5), (960, 2048, 1, 64, 8), (512, 3000, 40, 128, 6), (640, 5120, 130, 64, 16),
+    (1000, 4104, 7, 64, 5),
+]
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", SPLITK_CASES)
+@pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
+def test_spmm_few_tokens_split_k(out, inn, T, V, M, ydt):
+    """Few tokens: K is split over workgroups and the fp32 partial products are summed by a second
+    kernel.  Checked against the oracle, and -- with integer-valued operands, where every order of
+    summation is exact -- bit for bit against the same call without scratch (no split)."""
+    rng = np.random.default_rng(out + inn + T)
+    W = _rand_w(rng, out, inn, "normal")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    assert vnm.vnm_spmm_scratch_bytes(T, out) > 0
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=ydt, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
+    assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
+    Wi, Xi = syn.small_integer_case(out, inn, T, seed=T + M, lo=-2, hi=2)
+    ci = vnm.vnm_prune_compress(_dev(Wi), V, M, want_mask=True)
+    staged = vnm.vnm_stage_x(_dev(Xi), M)
+    Ya = vnm.vnm_spmm_staged(staged, T, ci, out_dtype=torch.float32)                      # default scratch: split
+    none = torch.empty(0, dtype=torch.uint8, device=DEV)
+    Yb = vnm.vnm_spmm_staged(staged, T, ci, out_dtype=torch.float32, scratch=none)        # no scratch: one pass
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
+    Yi_ref = orc.matmul_ref(Xi, orc.masked_dense(Wi, ci.mask.cpu().numpy()))
+    assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
+
+
 def test_spmm_pad_columns_are_never_read():
     """in = 72 at M = 5 pads to 75: the pad columns must count as zero even when the memory right
     after each X row holds NaN."""

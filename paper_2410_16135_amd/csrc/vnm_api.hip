@@ -95,6 +95,13 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
   hipStream_t st = (hipStream_t)stream;
   const bool fast_ok = packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d);
   if (path == VNM_PATH_SMFMAC && !fast_ok) return VNM_ERR_UNSUPPORTED;
+  if (path != VNM_PATH_GENERIC && fast_ok && T <= skinny_max_tokens()) {
+    // no staging; a workspace, if given, serves as split-K scratch (same offset as for larger T)
+    const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
+    const bool have = workspace && ((uintptr_t)workspace & 255) == 0 && workspace_bytes > sb;
+    return launch_spmm_skinny(X, T, ldx, packed, d, Y, ldy, y_dtype, have ? (char*)workspace + sb : nullptr,
+                              have ? workspace_bytes - sb : 0, st);
+  }
   if (path != VNM_PATH_GENERIC && fast_ok) {
     // the matrix-core kernel streams a re-laid copy of X that lives in the caller's workspace
     if (!workspace || workspace_bytes < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;

@@ -80,6 +80,14 @@ int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* value
                         hipStream_t st);
 int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st);
 bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d);
+// Single-kernel product for at most skinny_max_tokens() tokens, straight from X (no staging, no workspace).
+int64_t skinny_max_tokens();
+int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+                       void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
+                       hipStream_t st);
+// Y = sum of KS fp32 partial products [KS][T][out] held in `part`
+int launch_splitk_reduce(const void* part, int KS, int64_t T, int64_t out, void* Y, int64_t ldy,
+                         int y_dtype, hipStream_t st);
 // Split-K scratch of the product kernel for small token counts (fp32 partial products), 0 when unused.
 int64_t splitk_scratch_bytes(int64_t T, int64_t out);
 int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,

@@ -1,0 +1,247 @@
+// vnm_spmm for at most 32 tokens (decode, small batches): one kernel, no staging pass; a workspace is
+// optional (split K for few row blocks, see the launcher).
+//
+// With so few tokens the product is a stream of the compressed weight through the matrix cores at
+// HBM rate; what matters is that every byte of it is requested early and read once.  One workgroup
+// owns one row block of the packed copy (32 or 64 rows) and the whole K range; its 8 waves take the
+// K steps round-robin, each into private accumulators, and add them up through LDS at the end, so
+// no partial products leave the chip.  K is walked in phases of P steps: the A operands and the
+// slice of X of phase p+1 are requested before phase p is multiplied and are parked (X: in a
+// second LDS buffer) after it.  X stays token-major in LDS, [token][raw column] with an odd
+// number of dwords per row; a lane assembles its B operand -- for its token, the 4 kept columns
+// of 4 column blocks -- with 16 two-byte LDS reads at the offsets of the packed column table
+// (conflict-free: lanes differ in the row).  That is 16 LDS instructions per matrix instruction
+// pair, far below what the streaming rate needs; the transposing staged layout of the many-token
+// kernel would cost a second launch.
+#include <cstdlib>
+#include "vnm_internal.h"
+
+namespace vnm {
+
+typedef _Float16 sk_h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 sk_h16 __attribute__((ext_vector_type(16)));
+typedef float sk_f16 __attribute__((ext_vector_type(16)));
+typedef unsigned sk_u8 __attribute__((ext_vector_type(8)));
+
+constexpr int kSkWaves = 8;      // waves per workgroup
+constexpr int kSkSPW = 4;        // K steps per wave and phase, at most
+constexpr int kSkNX = 8;         // 16-byte pieces of X per thread and phase, at most
+
+struct SkinnyArgs {
+  const unsigned short* X; int64_t T, ldx, in;
+  const uint4* pa; const unsigned short* pidx; const uint4* pcol;
+  int64_t out, S;
+  int M, P;                      // P: K steps per phase, a multiple of 8, at most 32
+  void* Y; int64_t ldy; int y_fp32;
+  // split K: workgroup (r, z) walks phases [z * npz, min(nph, (z + 1) * npz)) and writes its fp32
+  // partial product at Y + z * z_stride elements (a scratch then; summed by splitk_reduce)
+  int npz; int64_t z_stride;
+};
+
+// AT: 32-row tiles per packed row block; TT: token rows held in LDS (16 or 32)
+template <int AT, int TT>
+__global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const SkinnyArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t r = blockIdx.x;
+  const int M = a.M, P = a.P;
+  const int64_t S = a.S;
+  const int ncolP = P * 8 * M;                       // raw columns of a phase
+  const int pitch = ncolP * 2 + 4;                   // bytes per token row: odd number of dwords
+  const int bufB = (TT * pitch + 15) & ~15;
+  const int nph_all = (int)((S + P - 1) / P);
+  const int p_begin = (int)blockIdx.y * a.npz;
+  const int p_end = p_begin + a.npz < nph_all ? p_begin + a.npz : nph_all;
+  const int spw = P / kSkWaves;
+  // X pieces of this thread: piece i is (token, chunk) number tid + 512 i in row-major order
+  const int CH = P * M;
+  const int tok_first = tid / CH, ch_first = tid - tok_first * CH;
+  const int dtok = 512 / CH, dch = 512 - dtok * CH;
+
+  uint4 xw[kSkNX];
+  auto load_x = [&](int p) {
+    const int64_t col0 = (int64_t)p * ncolP;
+    int tok = tok_first, ch = ch_first;
+#pragma unroll
+    for (int i = 0; i < kSkNX; ++i) {
+      xw[i] = make_uint4(0, 0, 0, 0);
+      if (tok < TT && tok < a.T && col0 + ch * 8 < a.in) xw[i] = *(const uint4*)(a.X + tok * a.ldx + col0 + ch * 8);
+      ch += dch; tok += dtok;
+      if (ch >= CH) { ch -= CH; ++tok; }
+    }
+  };
+  auto store_x = [&](int buf) {
+    int tok = tok_first, ch = ch_first;
+#pragma unroll
+    for (int i = 0; i < kSkNX; ++i) {
+      if (tok < TT) {
+        unsigned* d = (unsigned*)(smem + (size_t)buf * bufB + (size_t)tok * pitch + ch * 16);
+        d[0] = xw[i].x; d[1] = xw[i].y; d[2] = xw[i].z; d[3] = xw[i].w;
+      }
+      ch += dch; tok += dtok;
+      if (ch >= CH) { ch -= CH; ++tok; }
+    }
+  };
+
+  struct AOp { uint4 w[AT]; unsigned idx; uint4 pc; };
+  const int hB = lane >> 5;
+  auto load_a = [&](AOp (&o)[kSkSPW], int p) {
+#pragma unroll
+    for (int i = 0; i < kSkSPW; ++i) {
+      const int64_t s = (int64_t)p * P + wave + kSkWaves * i;
+      if (i < spw && s < S) {
+        const int64_t rs = r * S + s;
+#pragma unroll
+        for (int t = 0; t < AT; ++t) o[i].w[t] = a.pa[(rs * AT + t) * 64 + lane];
+        if (AT == 1) o[i].idx = a.pidx[rs * 64 + lane];
+        else o[i].idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
+        o[i].pc = a.pcol[rs * 2 + hB];
+      }
+    }
+  };
+
+  sk_f16 acc[AT];
+#pragma unroll
+  for (int t = 0; t < AT; ++t)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc[t][k] = 0.f;
+
+  const int tokl = (TT == 32) ? (lane & 31) : (lane & 15);      // TT = 16: lanes 16..31 repeat 0..15
+  auto compute = [&](const AOp (&o)[kSkSPW], int buf, int p) {
+#pragma unroll
+    for (int i = 0; i < kSkSPW; ++i) {
+      const int64_t s = (int64_t)p * P + wave + kSkWaves * i;
+      if (i < spw && s < S) {
+        const unsigned char* row = smem + (size_t)buf * bufB + (size_t)tokl * pitch + (size_t)(wave + kSkWaves * i) * 16 * M;
+        const unsigned pc[4] = {o[i].pc.x, o[i].pc.y, o[i].pc.z, o[i].pc.w};
+        sk_u8 bw;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          // element 4m + kq of the B operand: kept column kq of column block blk(m, h)
+          unsigned v[4];
+#pragma unroll
+          for (int kq = 0; kq < 4; ++kq) v[kq] = *(const unsigned short*)(row + 2 * ((pc[kq] >> (8 * m)) & 255u));
+          bw[2 * m] = v[0] | (v[1] << 16);
+          bw[2 * m + 1] = v[2] | (v[3] << 16);
+        }
+        const sk_h16 bv = __builtin_bit_cast(sk_h16, bw);
+        const int ix = (int)o[i].idx;
+        acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[0]), bv, acc[0], ix, 0, 0);
+        if (AT == 2)
+          acc[AT - 1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[AT - 1]), bv, acc[AT - 1], ix, 0, 1);
+      }
+    }
+  };
+
+  AOp cur[kSkSPW], nxt[kSkSPW];
+  load_x(p_begin);
+  load_a(cur, p_begin);
+  store_x(p_begin & 1);
+  __syncthreads();
+  for (int p = p_begin; p < p_end; ++p) {
+    const bool more = p + 1 < p_end;
+    if (more) { load_x(p + 1); load_a(nxt, p + 1); }
+    compute(cur, p & 1, p);
+    if (more) {
+      store_x((p + 1) & 1);
+#pragma unroll
+      for (int i = 0; i < kSkSPW; ++i) cur[i] = nxt[i];
+    }
+    __syncthreads();
+  }
+
+  // sum of the 8 waves' accumulators through LDS, [wave][token][rows + 1] fp32, then the store.
+  // Accumulator element j of lane l is row 8 (j / 4) + 4 (l / 32) + j % 4 of the tile, token l % 32.
+  constexpr int RW = AT * 32;
+  float* red = (float*)smem;
+  if ((lane & 31) < TT) {
+    float* mine = red + ((size_t)wave * TT + (lane & 31)) * (RW + 1);
+#pragma unroll
+    for (int t = 0; t < AT; ++t)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mine[t * 32 + 8 * (j >> 2) + 4 * hB + (j & 3)] = acc[t][j];
+  }
+  __syncthreads();
+  for (int e = tid; e < TT * RW; e += 64 * kSkWaves) {
+    const int tok = e / RW, rw = e - tok * RW;
+    const int64_t o = r * RW + rw;
+    if (tok < a.T && o < a.out) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kSkWaves; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
+      if (a.y_fp32) ((float*)a.Y)[(int64_t)blockIdx.y * a.z_stride + tok * a.ldy + o] = sum;
+      else ((_Float16*)a.Y)[tok * a.ldy + o] = (_Float16)sum;
+    }
+  }
+}
+
+int64_t skinny_max_tokens() { return 32; }
+
+template <int AT, int TT>
+static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t st) {
+  const size_t bufB = ((size_t)TT * (a.P * 16 * a.M + 4) + 15) & ~(size_t)15;
+  size_t lds = 2 * bufB;
+  const size_t red = (size_t)kSkWaves * TT * (AT * 32 + 1) * 4;
+  if (red > lds) lds = red;
+  auto kern = spmm_skinny_kernel<AT, TT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(spmm_skinny)"); return VNM_ERR_HIP; }
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS), dim3(64 * kSkWaves), lds, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
+int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+                       void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
+                       hipStream_t st) {
+  const PackedLayout pl = packed_layout(d);
+  const char* p = (const char*)packed;
+  const int VP = packed_v(d.V);
+  const int64_t R = d.R * (d.V / VP);
+  if (R > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
+  SkinnyArgs a;
+  a.X = (const unsigned short*)X; a.T = T; a.ldx = ldx; a.in = d.in;
+  a.pa = (const uint4*)(p + pl.pa_off);
+  a.pidx = (const unsigned short*)(p + pl.pidx_off);
+  a.pcol = (const uint4*)(p + pl.pcol_off);
+  a.out = d.out; a.S = d.S; a.M = d.M;
+  a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
+  const int TT = T <= 16 ? 16 : 32;
+  // steps per phase: a multiple of the 8 waves, at most 32, with at most kSkNX pieces of X per thread
+  // (TT * P * M <= 512 * kSkNX), which also keeps the two LDS buffers below 132 KiB
+  int P = 512 * kSkNX / (TT * d.M) / 8 * 8;
+  P = P > 32 ? 32 : (P < 8 ? 8 : P);
+  a.P = P;
+  // A workgroup's phases run one memory round trip after the other, so a long K on few row blocks
+  // is latency-bound.  With scratch, and while all workgroups still fit the 256 CUs at once (a second
+  // round costs more than it saves), K is split over several workgroups per row block; their fp32
+  // partial products are summed by a second kernel.
+  const int nph = (int)((d.S + P - 1) / P);
+  int KS = 1;
+  a.npz = nph; a.z_stride = 0;
+  if (scratch && nph > 1 && R <= 128) {
+    int64_t ks = 256 / R;
+    if (ks > 16) ks = 16;
+    if (ks > nph) ks = nph;
+    while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
+    if (const char* e = getenv("VNM_SKINNY_KS")) { const int k = atoi(e); if (k >= 1 && k <= ks) ks = k; }
+    if (ks > 1) {
+      a.npz = (int)((nph + ks - 1) / ks);
+      KS = (nph + a.npz - 1) / a.npz;
+    }
+  }
+  if (KS > 1) { a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out; }
+  int rc = VNM_ERR_UNSUPPORTED;
+  if (VP == 64) rc = TT == 16 ? launch_skinny_cfg<2, 16>(a, R, KS, st) : launch_skinny_cfg<2, 32>(a, R, KS, st);
+  if (VP == 32) rc = TT == 16 ? launch_skinny_cfg<1, 16>(a, R, KS, st) : launch_skinny_cfg<1, 32>(a, R, KS, st);
+  if (rc != VNM_OK || KS == 1) return rc;
+  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);
+}
+
+}  // namespace vnm

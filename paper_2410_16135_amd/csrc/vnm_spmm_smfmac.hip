@@ -618,13 +618,18 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
       break;
   }
   if (rc != VNM_OK || KS == 1) return rc;
-  const int64_t n = T * d.out;
+  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);
+}
+
+int launch_splitk_reduce(const void* part, int KS, int64_t T, int64_t out, void* Y, int64_t ldy,
+                         int y_dtype, hipStream_t st) {
+  const int64_t n = T * out;
   if (y_dtype == 0)
     hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       (const float*)scratch, KS, T, d.out, (_Float16*)Y, ldy);
+                       (const float*)part, KS, T, out, (_Float16*)Y, ldy);
   else
     hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       (const float*)scratch, KS, T, d.out, (float*)Y, ldy);
+                       (const float*)part, KS, T, out, (float*)Y, ldy);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "splitk_reduce_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

@@ -78,8 +78,8 @@ def test_argument_errors(lib):
     assert lib.vnm_pack(good, good, good, 128, 128, 64, 2, 8, P(0x1008), None) == 4
     # the matrix-core kernel needs its workspace: missing or short workspace is an error, not a silent fallback
     a256 = P(0x1000)
-    assert lib.vnm_spmm(good, 4, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 5
-    assert lib.vnm_spmm(good, 4, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, a256, 16, None) == 5
+    assert lib.vnm_spmm(good, 64, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, None, 0, None) == 5
+    assert lib.vnm_spmm(good, 64, 128, good, good, good, a256, 128, 128, 64, 2, 8, good, 128, 0, 0, a256, 16, None) == 5
     b = ctypes.c_int64(-1)
     assert lib.vnm_spmm_workspace_bytes(4096, 4096, 4096, 64, 2, 5, ctypes.byref(b)) == 0 and b.value == (32 * 103 + 3) * 13312
     assert lib.vnm_spmm_workspace_bytes(16, 128, 128, 16, 2, 8, ctypes.byref(b)) == 0 and b.value == 0

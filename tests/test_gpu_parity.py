@@ -272,3 +272,30 @@ def test_llama_shaped_layers_sampled_tokens(which):
     Y_ref = orc.matmul_ref(X[tok], Wm)
     err = orc.max_normalised_error(Y[torch.from_numpy(tok).to(DEV)].float().cpu().numpy(), Y_ref)
     assert err <= TOL, err
+
+
+SWEEP_POINTS = [
+    # (layer index in the sweep's two shapes: 0 = 11008 x 4096, 1 = 4096 x 11008), V, M, tokens
+    (0, 128, 16, 4096), (1, 32, 8, 4096), (0, 64, 7, 16), (1, 128, 5, 16), (1, 64, 4, 1),
+]
+
+
+@pytest.mark.parametrize("shape,V,M,T", SWEEP_POINTS)
+def test_sweep_points_full_size(shape, V, M, T):
+    """Points of the V x M x tokens sweep at full layer size: 128-row patterns (stored as 64-row
+    blocks in the matrix-core copy), 32-row patterns, and the few-token kernel with and without
+    split K.  Compression is checked bit for bit, the product on up to 128 sampled tokens."""
+    name = ("gate", "down")[shape]
+    layer = next(L for L in syn.config_sweep() if L.name == f"{name}_V{V}_M{M}_T{max(T, 16)}")
+    W, X = syn.layer_tensors(layer, tokens=T)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, V, M)
+    Wm = orc.masked_dense(W, mask)
+    rng = np.random.default_rng(7)
+    tok = np.sort(rng.choice(T, size=min(T, 128), replace=False))
+    tok[0], tok[-1] = 0, T - 1
+    Y_ref = orc.matmul_ref(X[tok], Wm)
+    err = orc.max_normalised_error(Y[torch.from_numpy(tok).to(DEV)].float().cpu().numpy(), Y_ref)
+    assert err <= TOL, err

@@ -10,6 +10,8 @@ Everything here follows the paper's own wording of the method:
 * Section 3 ("Pruning of V:N:M sparsity"): the three pruning steps
   (importance score, column pruning per V x M block by column L1 norm,
   2:4 inside the four surviving columns of every row).
+* Section 3, Eq. 1: the RIA importance score (importance_ria) as an
+  alternative to |w|; prune() and compress() take any score matrix.
 * Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
   input dimension is a multiple of M and the output dimension a multiple of V.
 * Appendix A: the compressed triple -- the compact kept values (A_n), the four
@@ -28,7 +30,9 @@ summation order; the column norms below are therefore exact.
 Pins (tests/test_oracle_pins.py): pattern invariants, brute-force enumeration
 on tiny blocks, optimality of the kept mass, the M = 4 (plain 2:4) and V = 1
 (2-of-M per row) special cases, a hand-worked example, round trips, exact
-integer column sums, and for the matmul a triple-loop dot product, one-hot
+integer column sums, for the scored path its reduction to ABS when the score
+is |w|, brute force with random scores, and a hand-worked RIA example with
+closed forms and invariances, and for the matmul a triple-loop dot product, one-hot
 inputs and exactly representable small-integer products.  No function in this
 file is "parity unpinned"; the paper itself prints no numeric example of a
 pruned block (its figures are not part of the text), so the worked example is
@@ -78,6 +82,31 @@ def importance_abs(Wp: np.ndarray) -> np.ndarray:
     return np.abs(Wp.astype(np.float64))
 
 
+def importance_ria(W: np.ndarray, act: np.ndarray) -> np.ndarray:
+    """Step 1 of Section 3 with the RIA criterion (Eq. 1), as fp32 scores [out x in]:
+
+        RIA[i, j] = (|W[i,j]| / sum_i' |W[i',j]|  +  |W[i,j]| / sum_j' |W[i,j']|) * act[j]
+
+    act[j] = (L2 norm of the activations of input channel j) ** a is an input (fp32 [in]); the
+    equation's activation factor is taken per input channel j, as in the criterion it cites.
+    The two sums are exact (integers, in units of 2**-24); every later operation is one IEEE
+    fp64 operation -- convert, divide, divide, add, multiply -- followed by one rounding to
+    fp32, so the scores are reproducible bit for bit.  A term whose sum is zero is zero.
+    """
+    W = _as_fp16_matrix(W)
+    act = np.asarray(act)
+    if act.dtype != np.float32 or act.shape != (W.shape[1],):
+        raise TypeError("act: float32 vector of length in")
+    units = np.rint(np.abs(W.astype(np.float64)) * 2.0 ** 24).astype(np.int64)     # exact
+    col = units.sum(axis=0, dtype=np.int64)
+    row = units.sum(axis=1, dtype=np.int64)
+    a = units.astype(np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q_col = np.where(col[None, :] > 0, a / col.astype(np.float64)[None, :], 0.0)
+        q_row = np.where(row[:, None] > 0, a / row.astype(np.float64)[:, None], 0.0)
+    return ((q_col + q_row) * act.astype(np.float64)[None, :]).astype(np.float32)
+
+
 def column_l1(S: np.ndarray, V: int, M: int) -> np.ndarray:
     """Step 2 of Section 3: L1 norm of every column of every V x M block.
 
@@ -87,6 +116,19 @@ def column_l1(S: np.ndarray, V: int, M: int) -> np.ndarray:
     out_pad, in_pad = S.shape
     R, B = out_pad // V, in_pad // M
     return S.reshape(R, V, B, M).sum(axis=1)
+
+
+def column_l1_in_row_order(S: np.ndarray, V: int, M: int) -> np.ndarray:
+    """Column L1 norms for a general score matrix: the same sums as column_l1, added in fp64
+    one row after the other (v = 0, 1, ..., V-1).  Sums of arbitrary fp32 scores can depend on
+    the order of addition in their last bit; fixing the order makes the selection unique."""
+    out_pad, in_pad = S.shape
+    R, B = out_pad // V, in_pad // M
+    blk = S.reshape(R, V, B, M)
+    L = np.zeros((R, B, M), dtype=np.float64)
+    for v in range(V):
+        L = L + blk[:, v, :, :]
+    return L
 
 
 def select_columns(L: np.ndarray) -> np.ndarray:
@@ -120,19 +162,22 @@ def select_2_of_4(S: np.ndarray, colidx: np.ndarray, V: int, M: int) -> np.ndarr
 def prune(W: np.ndarray, V: int, M: int, score: np.ndarray | None = None):
     """The pruning operator S_{V:N:M} of Section 3 with N = 2.
 
-    W: fp16 [out x in].  score: optional fp64 [out x in] importance scores
-    (default: ABS).  Returns (colidx [R,B,4] u8, pos [out_pad,B,2] u8,
-    mask [out x in] u8).
+    W: fp16 [out x in].  score: optional [out x in] importance scores, finite
+    and non-negative (default: ABS); they are padded with zeros like W, their
+    column norms are added in row order (column_l1_in_row_order), and step 3
+    compares the scores themselves.  Returns (colidx [R,B,4] u8,
+    pos [out_pad,B,2] u8, mask [out x in] u8).
     """
     W = _as_fp16_matrix(W)
     out, inn = W.shape
     out_pad, in_pad, R, B = padded_dims(out, inn, V, M)
     if score is None:
         S = importance_abs(pad_weight(W, V, M))
+        L = column_l1(S, V, M)
     else:
         S = np.zeros((out_pad, in_pad), dtype=np.float64)
         S[:out, :inn] = np.asarray(score, dtype=np.float64)
-    L = column_l1(S, V, M)
+        L = column_l1_in_row_order(S, V, M)
     colidx = select_columns(L)
     pos = select_2_of_4(S, colidx, V, M)
     mask = mask_from_selection(colidx, pos, out, inn, V, M)

@@ -339,3 +339,121 @@ def test_config0_shapes():
     assert values.shape == (128, 32) and meta.shape == (128, 8) and colidx.shape == (2, 16, 4)
     assert mask.sum() == 128 * 128 // 4
     assert abs(float(W.astype(np.float64).std()) - 0.02) < 0.002
+
+
+# ------------------------------------------------------- scored pruning and RIA (Section 3, Eq. 1)
+
+@pytest.mark.parametrize("out,inn,V,M", [(128, 128, 64, 8), (64, 37, 16, 5), (96, 50, 32, 7), (40, 64, 8, 4)])
+@pytest.mark.parametrize("kind", ["normal", "ints", "binary"])
+def test_scored_prune_with_abs_scores_is_the_abs_prune(out, inn, V, M, kind):
+    """|w| handed in as an fp32 score matrix must reproduce the ABS pruning exactly (the fp32
+    copies are exact, and so are their column sums in any order)."""
+    rng = np.random.default_rng(out + inn + V + M)
+    W = _rand_w(rng, out, inn, kind)
+    ref = orc.compress(W, V, M)
+    got = orc.compress(W, V, M, score=np.abs(W).astype(np.float32))
+    for a, b in zip(ref, got):
+        assert np.array_equal(a.view(np.uint16) if a.dtype == np.float16 else a,
+                              b.view(np.uint16) if b.dtype == np.float16 else b)
+
+
+def _brute_block_scored(Sb):
+    V, M = Sb.shape
+    A = [[_exact(Sb[v, c]) for c in range(M)] for v in range(V)]
+    L = [sum(A[v][c] for v in range(V)) for c in range(M)]
+    best = max(itertools.combinations(range(M), 4),
+               key=lambda s: (sum(L[c] for c in s), tuple(-c for c in s)))
+    rows = []
+    for v in range(V):
+        g = [A[v][c] for c in best]
+        rows.append(max(itertools.combinations(range(4), 2),
+                        key=lambda p: (g[p[0]] + g[p[1]], (-p[0], -p[1]))))
+    return best, rows
+
+
+@pytest.mark.parametrize("V", [1, 2, 4])
+@pytest.mark.parametrize("M", [4, 5, 7])
+@pytest.mark.parametrize("kind", ["dyadic", "ints"])
+def test_scored_brute_force_tiny_blocks(V, M, kind):
+    """Scores unrelated to |w| (so that a mix-up of W and the score shows): enumeration of all
+    column subsets and row pairs in exact arithmetic.  Scores are dyadic, their sums exact."""
+    rng = np.random.default_rng(77 * V + M + len(kind))
+    R, B = 3, 4
+    W = _rand_w(rng, R * V, B * M, "normal")
+    if kind == "dyadic":
+        S = (rng.integers(0, 1 << 12, size=W.shape) / 256.0).astype(np.float32)
+    else:
+        S = rng.integers(0, 3, size=W.shape).astype(np.float32)
+    colidx, pos, mask = orc.prune(W, V, M, score=S)
+    for r in range(R):
+        for b in range(B):
+            best, rows = _brute_block_scored(S[r * V:(r + 1) * V, b * M:(b + 1) * M])
+            assert tuple(int(c) for c in colidx[r, b]) == best
+            for v in range(V):
+                assert tuple(int(p) for p in pos[r * V + v, b]) == rows[v]
+    values, meta, ci, _ = orc.compress(W, V, M, score=S)
+    assert np.array_equal(orc.decompress(values, meta, ci, R * V, B * M, V, M).view(np.uint16),
+                          orc.masked_dense(W, mask).view(np.uint16))
+
+
+def test_scored_column_sums_are_added_in_row_order():
+    """A column whose fp64 sum depends on the order of addition: 2^53 + 1 + 1 is 2^53 when the
+    large term comes first (each 1 is rounded away) and 2^53 + 2 when it comes last."""
+    V, M = 3, 4
+    S = np.zeros((V, M), dtype=np.float64)
+    S[:, 0] = [2.0 ** 53, 1.0, 1.0]
+    S[:, 1] = [0.5, 0.0, 0.0]
+    assert np.array_equal(S.astype(np.float32).astype(np.float64), S)      # all are fp32 values
+    assert orc.column_l1_in_row_order(S, V, M)[0, 0, 0] == 2.0 ** 53
+    assert orc.column_l1_in_row_order(S[::-1].copy(), V, M)[0, 0, 0] == 2.0 ** 53 + 2.0
+    assert orc.column_l1_in_row_order(S, V, M)[0, 0, 1] == 0.5
+
+
+def test_ria_hand_worked_example():
+    with open(os.path.join(GOLDEN, "ria_example.json")) as f:
+        g = json.load(f)
+    W = np.array(g["W"], dtype=np.float16)
+    act = np.array(g["act"], dtype=np.float32)
+    S = orc.importance_ria(W, act)
+    exp = np.array([[float(Fraction(x)) for x in row] for row in g["score_fractions"]], dtype=np.float64)
+    assert S.dtype == np.float32 and S.shape == W.shape
+    assert np.allclose(S.astype(np.float64), exp, rtol=2.0 ** -23, atol=0)
+
+
+def test_ria_closed_forms_and_invariances():
+    rng = np.random.default_rng(5)
+    out, inn = 24, 40
+    act = (rng.random(inn) + 0.5).astype(np.float32)
+    # all magnitudes equal: every weight gets (1/out + 1/in) * act_j, whatever the signs
+    W = (np.float16(0.375) * rng.choice([-1.0, 1.0], size=(out, inn))).astype(np.float16)
+    S = orc.importance_ria(W, act)
+    exp = ((1.0 / out + 1.0 / inn) * act.astype(np.float64)).astype(np.float32)
+    assert np.allclose(S, np.broadcast_to(exp, S.shape), rtol=2.0 ** -22, atol=0)
+    # rank one, W = u v^T with positive factors: (u_i / sum u + v_j / sum v) * act_j
+    u = 2.0 ** rng.integers(-3, 3, size=out)
+    v = 2.0 ** rng.integers(-3, 3, size=inn)
+    W = np.outer(u, v).astype(np.float16)
+    S = orc.importance_ria(W, act)
+    exp = (u[:, None] / u.sum() + v[None, :] / v.sum()) * act.astype(np.float64)[None, :]
+    assert np.allclose(S.astype(np.float64), exp, rtol=2.0 ** -22, atol=0)
+    # scaling W by a power of two changes nothing, bit for bit; permutations permute the scores
+    W = _rand_w(rng, out, inn, "normal")
+    S = orc.importance_ria(W, act)
+    assert np.array_equal(orc.importance_ria((W.astype(np.float32) * 4.0).astype(np.float16), act), S)
+    pr, pc = rng.permutation(out), rng.permutation(inn)
+    assert np.array_equal(orc.importance_ria(W[pr][:, pc], act[pc]), S[pr][:, pc])
+    # the activation factor multiplies its input channel (column), nothing else
+    act2 = act.copy(); act2[3] *= np.float32(2.0)
+    S2 = orc.importance_ria(W, act2)
+    assert np.array_equal(S2[:, 3], S[:, 3] * np.float32(2.0))
+    assert np.array_equal(np.delete(S2, 3, axis=1), np.delete(S, 3, axis=1))
+
+
+def test_ria_zero_rows_and_columns_give_zero_scores():
+    rng = np.random.default_rng(6)
+    W = _rand_w(rng, 16, 20, "normal")
+    W[:, 4] = 0; W[7, :] = 0
+    S = orc.importance_ria(W, np.ones(20, dtype=np.float32))
+    assert np.all(np.isfinite(S)) and np.all(S[:, 4] == 0) and np.all(S[7, :] == 0) and np.all(S >= 0)
+    colidx, pos, mask = orc.prune(W, 8, 5, score=S)
+    assert mask.reshape(2, 8, 4, 5).sum(axis=3).max() == 2           # still 2 per row and block

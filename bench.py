@@ -249,6 +249,36 @@ def main():
         "calibration_copy": {"bytes_read": calib_bytes, "bytes_written": calib_bytes,
                              "what": "one torch copy_ of the first layer's W after the timed region"},
     }
+    if not args.spmm_only:
+        # next row after the hot path (not part of `value`): RIA scores (Eq. 1) and pruning driven
+        # by them, on the first layer; and the few-token product (decode) on the same layer
+        L, Wd, Xd, c, Y, Wout = state[0]
+        act = Xd.float().pow(2).sum(dim=0).sqrt().pow(0.5).contiguous()
+        S = vnm.vnm_ria_scores(Wd, act)
+        cs = vnm.vnm_prune_compress_scored(Wd, S, L.V, L.M)
+        X16 = Xd[:16].contiguous()
+        Y16 = torch.empty((16, L.out), dtype=torch.float16, device=dev)
+
+        def timed(f, n=10):
+            f(); torch.cuda.synchronize()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(n):
+                f()
+            b.record(); torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+        w_bytes = L.out * L.inn * 2
+        t_ria = timed(lambda: vnm.vnm_ria_scores(Wd, act, S=S))
+        t_ps = timed(lambda: vnm.vnm_prune_compress_scored(Wd, S, L.V, L.M, out=cs))
+        t_16 = timed(lambda: vnm.vnm_spmm(X16, c, Y=Y16), n=30)
+        t_16d = timed(lambda: torch.matmul(X16, Wd.t(), out=Y16), n=30)
+        result["beyond_hot_path"] = {
+            "layer": L.name, "ria_scores_ms": t_ria, "prune_compress_scored_ms": t_ps,
+            "ria_scores_gbps": (2 * w_bytes + 2 * w_bytes) / t_ria / 1e6,
+            "prune_compress_scored_gbps": (w_bytes + 2 * w_bytes) / t_ps / 1e6,
+            "spmm_16_tokens_ms": t_16, "dense_16_tokens_ms": t_16d,
+            "note": "HIP-event means including launch gaps; bytes counted: RIA reads W twice and writes fp32 "
+                    "scores; scored pruning reads W and the scores"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(layers)
     print(json.dumps(result))

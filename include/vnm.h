@@ -89,6 +89,32 @@ int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_t ldw, int 
                        void* values, void* meta, void* colidx, void* mask, void* packed,
                        void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Section 3, step 1 with the RIA criterion (Eq. 1): fp32 scores
+ *   S[i, j] = (|W[i,j]| / sum_i' |W[i',j]| + |W[i,j]| / sum_j' |W[i,j']|) * act[j],
+ * act[j] = (L2 norm of the activations of input channel j)^a supplied by the caller (dev fp32 [in]).
+ * The two sums are exact; each score is five single IEEE fp64 operations (convert, divide, divide,
+ * add, multiply) and one rounding to fp32, so the result is reproducible bit for bit.  A term whose
+ * sum is zero counts as zero.
+ *   S          dev fp32 [out x in], leading dimension lds >= in
+ *   workspace  dev, 8-byte aligned, (out + in) * 8 bytes; contents are scratch
+ */
+int vnm_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act,
+                   void* S, int64_t lds, void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
+ * vnm_prune_compress with the importance scores handed in (Section 3, steps 2-3 on any score):
+ * S, dev fp32 [out x in] (leading dimension lds), finite and non-negative, zero-padded like W.
+ * Column L1 norms of the scores are added in fp64 in row order (row 0 of the block first), which
+ * fixes the selection where the order of addition would matter; step 3 compares the scores
+ * themselves; ties go to the lower index in both steps; the kept values are W's.  Outputs as
+ * for vnm_prune_compress (`colidx` 4-byte aligned).  Other scores: result unspecified, no fault.
+ */
+int vnm_prune_compress_scored(const void* W, const void* S, int64_t out, int64_t in,
+                              int64_t ldw, int64_t lds, int V, int N, int M,
+                              void* values, void* meta, void* colidx, void* mask, void* packed,
+                              void* stream);
+
 /* Builds `packed` from an existing canonical triple (e.g. one loaded from storage). */
 int vnm_pack(const void* values, const void* meta, const void* colidx,
              int64_t out, int64_t in, int V, int N, int M, void* packed, void* stream);

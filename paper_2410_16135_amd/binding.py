@@ -51,6 +51,10 @@ def load_library():
     lib.vnm_spmm_staged.restype = ci
     lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_workspace_bytes.restype = ci
+    lib.vnm_ria_scores.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp]
+    lib.vnm_ria_scores.restype = ci
+    lib.vnm_prune_compress_scored.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.vnm_prune_compress_scored.restype = ci
     lib.vnm_stage_x_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(i64)]
     lib.vnm_stage_x_bytes.restype = ci
     lib.vnm_spmm_scratch_bytes.argtypes = [i64, i64, ctypes.POINTER(i64)]
@@ -129,6 +133,38 @@ def vnm_prune_compress(W, V: int, M: int, N: int = 2, want_mask: bool = False, w
     _check(load_library().vnm_prune_compress(
         _ptr(W), o, i, W.stride(0), V, N, M, _ptr(out.values), _ptr(out.meta), _ptr(out.colidx),
         _ptr(out.mask), _ptr(out.packed), None, 0, _stream(W)), "vnm_prune_compress")
+    return out
+
+
+def vnm_ria_scores(W, act, S=None):
+    """fp32 RIA scores [out x in] of W (fp16 CUDA) for the activation factors act (fp32 CUDA [in])."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    assert act.is_cuda and act.dtype == torch.float32 and act.shape == (W.shape[1],) and act.is_contiguous()
+    o, i = W.shape
+    if S is None:
+        S = torch.empty((o, i), dtype=torch.float32, device=W.device)
+    ws = torch.empty((o + i) * 8, dtype=torch.uint8, device=W.device)
+    _check(load_library().vnm_ria_scores(_ptr(W), o, i, W.stride(0), _ptr(act), _ptr(S), S.stride(0), _ptr(ws),
+                                         ws.numel(), _stream(W)), "vnm_ria_scores")
+    return S
+
+
+def vnm_prune_compress_scored(W, S, V: int, M: int, N: int = 2, want_mask: bool = False,
+                              want_packed: bool = True, out=None) -> Compressed:
+    """vnm_prune_compress driven by the fp32 score matrix S [out x in] instead of |W|."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    assert S.is_cuda and S.dtype == torch.float32 and S.shape == W.shape and S.stride(1) == 1
+    o, i = W.shape
+    sizes = vnm_query_sizes(o, i, V, M, N)
+    if out is None:
+        values, meta, colidx, packed = _alloc(sizes, W.device, want_packed)
+        mask = torch.empty((o, i), dtype=torch.uint8, device=W.device) if want_mask else None
+        out = Compressed(values, meta, colidx, packed, o, i, V, M, mask)
+    _check(load_library().vnm_prune_compress_scored(
+        _ptr(W), _ptr(S), o, i, W.stride(0), S.stride(0), V, N, M, _ptr(out.values), _ptr(out.meta),
+        _ptr(out.colidx), _ptr(out.mask), _ptr(out.packed), _stream(W)), "vnm_prune_compress_scored")
     return out
 
 

@@ -63,6 +63,37 @@ extern "C" int vnm_prune_compress(const void* W, int64_t out, int64_t in, int64_
   return rc;
 }
 
+extern "C" int vnm_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act,
+                              void* S, int64_t lds, void* workspace, int64_t workspace_bytes,
+                              void* stream) {
+  if (!W || !act || !S || !workspace) return VNM_ERR_NULL;
+  if (out <= 0 || in <= 0 || ldw < in || lds < in) return VNM_ERR_SHAPE;
+  if (workspace_bytes < (out + in) * 8) return VNM_ERR_WORKSPACE;
+  if (((uintptr_t)W & 1) || ((uintptr_t)act & 3) || ((uintptr_t)S & 3) || ((uintptr_t)workspace & 7)) return VNM_ERR_ALIGN;
+  return launch_ria_scores(W, out, in, ldw, act, S, lds, workspace, (hipStream_t)stream);
+}
+
+extern "C" int vnm_prune_compress_scored(const void* W, const void* S, int64_t out, int64_t in,
+                                         int64_t ldw, int64_t lds, int V, int N, int M, void* values,
+                                         void* meta, void* colidx, void* mask, void* packed,
+                                         void* stream) {
+  if (!W || !S || !values || !meta || !colidx) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (ldw < in || lds < in) return VNM_ERR_SHAPE;
+  if (((uintptr_t)W & 1) || ((uintptr_t)S & 3) || ((uintptr_t)values & 3) || ((uintptr_t)colidx & 3)) return VNM_ERR_ALIGN;
+  const Dims d = make_dims(out, in, V, M);
+  if (packed) {
+    if (!has_packed(V, M)) return VNM_ERR_UNSUPPORTED;
+    if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  rc = launch_prune_scored(W, ldw, S, lds, d, values, meta, colidx, mask, st);
+  if (rc) return rc;
+  if (packed) return launch_pack(values, meta, colidx, d, packed, st);
+  return VNM_OK;
+}
+
 extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx, int64_t out,
                         int64_t in, int V, int N, int M, void* packed, void* stream) {
   if (!values || !meta || !colidx || !packed) return VNM_ERR_NULL;

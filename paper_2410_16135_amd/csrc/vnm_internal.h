@@ -80,6 +80,11 @@ int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* value
                         hipStream_t st);
 int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st);
 bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d);
+// Importance scores other than |w| (vnm_score.hip)
+int launch_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act, void* S,
+                      int64_t lds, void* workspace, hipStream_t st);
+int launch_prune_scored(const void* W, int64_t ldw, const void* S, int64_t lds, const Dims& d, void* values,
+                        void* meta, void* colidx, void* mask, hipStream_t st);
 // Single-kernel product for at most skinny_max_tokens() tokens, straight from X (no staging, no workspace).
 int64_t skinny_max_tokens();
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,

@@ -25,6 +25,7 @@ def test_exports_every_declared_symbol(lib):
     names = set(re.findall(r"\b(vnm_[a-z_]+)\s*\(", text))
     assert {"vnm_query_sizes", "vnm_prune_compress", "vnm_pack", "vnm_spmm", "vnm_decompress", "vnm_stage_x",
             "vnm_spmm_staged", "vnm_spmm_workspace_bytes", "vnm_stage_x_bytes", "vnm_spmm_scratch_bytes",
+            "vnm_ria_scores", "vnm_prune_compress_scored",
             "vnm_status_string", "vnm_last_hip_error", "vnm_format_version"} <= names
     for n in names:
         assert hasattr(lib, n), n
@@ -98,6 +99,15 @@ def test_argument_errors(lib):
     assert lib.vnm_stage_x_bytes(16, 4096, 5, ctypes.byref(sb)) == 0 and sb.value == (103 + 3) * 13312
     assert lib.vnm_spmm_workspace_bytes(16, 11008, 4096, 64, 2, 5, ctypes.byref(b)) == 0 and b.value == sb.value + kb.value
     assert lib.vnm_stage_x_bytes(16, 4096, 17, ctypes.byref(sb)) == 3
+    # scores
+    assert lib.vnm_ria_scores(None, 8, 8, 8, good, good, 8, good, 128, None) == 1
+    assert lib.vnm_ria_scores(good, 8, 8, 4, good, good, 8, good, 128, None) == 2            # ldw < in
+    assert lib.vnm_ria_scores(good, 8, 8, 8, good, good, 8, good, 127, None) == 5            # (out + in) * 8 bytes needed
+    assert lib.vnm_ria_scores(good, 8, 8, 8, P(0x1002), good, 8, good, 128, None) == 4
+    assert lib.vnm_prune_compress_scored(good, None, 128, 128, 128, 128, 64, 2, 8, good, good, good, None, None, None) == 1
+    assert lib.vnm_prune_compress_scored(good, good, 128, 128, 128, 100, 64, 2, 8, good, good, good, None, None, None) == 2
+    assert lib.vnm_prune_compress_scored(good, good, 128, 128, 128, 128, 64, 3, 8, good, good, good, None, None, None) == 3
+    assert lib.vnm_prune_compress_scored(good, P(0x1002), 128, 128, 128, 128, 64, 2, 8, good, good, good, None, None, None) == 4
     assert lib.vnm_status_string(0) == b"ok" and b"null" in lib.vnm_status_string(1)
 
 

@@ -299,3 +299,86 @@ def test_sweep_points_full_size(shape, V, M, T):
     Y_ref = orc.matmul_ref(X[tok], Wm)
     err = orc.max_normalised_error(Y[torch.from_numpy(tok).to(DEV)].float().cpu().numpy(), Y_ref)
     assert err <= TOL, err
+
+
+# ------------------------------------------------------- scored pruning and RIA (Section 3, Eq. 1)
+
+def _check_compressed_scored(c, W, S, V, M):
+    values, meta, colidx, mask = orc.compress(W, V, M, score=S)
+    assert np.array_equal(c.colidx.cpu().numpy(), colidx.reshape(-1)), "colidx"
+    assert np.array_equal(c.meta.cpu().numpy(), meta.reshape(-1)), "meta"
+    assert np.array_equal(c.values.cpu().numpy().view(np.uint16), values.reshape(-1).view(np.uint16)), "values"
+    assert np.array_equal(c.mask.cpu().numpy(), mask), "mask"
+    return mask
+
+
+@pytest.mark.parametrize("out,inn", [(128, 128), (70, 333), (200, 77), (1, 8), (257, 1030)])
+@pytest.mark.parametrize("kind", ["normal", "wide", "ints"])
+def test_ria_scores_bit_exact(out, inn, kind):
+    rng = np.random.default_rng(out * 3 + inn)
+    W = _rand_w(rng, out, inn, kind)
+    if kind == "ints":
+        W[:, inn // 2] = 0          # a zero column and a zero row: their terms count as zero
+        W[out // 2, :] = 0
+    act = (rng.random(inn) * 4.0 + 0.01).astype(np.float32)
+    S = vnm.vnm_ria_scores(_dev(W), _dev(act))
+    torch.cuda.synchronize()
+    S_ref = orc.importance_ria(W, act)
+    assert np.array_equal(S.cpu().numpy().view(np.uint32), S_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("out,inn,V,M", [(128, 128, 64, 8), (64, 40, 16, 5), (200, 333, 32, 5), (130, 77, 64, 7),
+                                         (256, 96, 128, 6), (48, 200, 16, 33)])
+@pytest.mark.parametrize("score", ["ria", "foreign", "ties", "order"])
+def test_prune_compress_scored_bit_exact(out, inn, V, M, score):
+    rng = np.random.default_rng(out + inn * 5 + V + M)
+    W = _rand_w(rng, out, inn, "normal")
+    if score == "ria":
+        S = orc.importance_ria(W, (rng.random(inn) * 2.0 + 0.1).astype(np.float32))
+    elif score == "foreign":     # unrelated to |w|: a mix-up of W and S cannot pass
+        S = rng.random((out, inn)).astype(np.float32)
+    elif score == "ties":
+        S = rng.integers(0, 3, size=(out, inn)).astype(np.float32)
+    else:                        # column sums that depend on the order of addition
+        S = (rng.random((out, inn)) * 10.0 ** rng.integers(-3, 12, size=(out, inn))).astype(np.float32)
+    c = vnm.vnm_prune_compress_scored(_dev(W), _dev(S), V, M, want_mask=True)
+    torch.cuda.synchronize()
+    mask = _check_compressed_scored(c, W, S, V, M)
+    Wd = vnm.vnm_decompress(c).cpu().numpy()
+    assert np.array_equal(Wd.view(np.uint16), orc.masked_dense(W, mask).view(np.uint16))
+    if c.packed is not None and inn % 8 == 0:
+        X = rng.standard_normal((33, inn)).astype(np.float16)
+        Y = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+        Y_ref = orc.matmul_ref(X, orc.masked_dense(W, mask))
+        assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
+
+
+def test_scored_path_strided_and_abs_equivalence():
+    """Row strides larger than the width, and |w| as the score reproduces vnm_prune_compress."""
+    rng = np.random.default_rng(8)
+    out, inn, V, M = 96, 120, 32, 5
+    Wbig = _dev(_rand_w(rng, out, inn + 24, "normal"))
+    Sbig = torch.rand((out, inn + 40), device=DEV, dtype=torch.float32)
+    Wv, Sv = Wbig[:, :inn], Sbig[:, :inn]
+    c = vnm.vnm_prune_compress_scored(Wv, Sv, V, M, want_mask=True)
+    torch.cuda.synchronize()
+    _check_compressed_scored(c, Wv.cpu().numpy(), Sv.cpu().numpy(), V, M)
+    Wn = Wv.cpu().numpy()
+    c_abs = vnm.vnm_prune_compress(Wv, V, M, want_mask=True)
+    c_s = vnm.vnm_prune_compress_scored(Wv, Wv.abs().float(), V, M, want_mask=True)
+    torch.cuda.synchronize()
+    for a, b in ((c_abs.values, c_s.values), (c_abs.meta, c_s.meta), (c_abs.colidx, c_s.colidx), (c_abs.mask, c_s.mask)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    _check_compressed(c_abs, Wn, V, M)
+
+
+def test_ria_prune_llama_shaped_layer_full_size():
+    layer = syn.config_llama2_7b()[0]
+    W, X = syn.layer_tensors(layer, tokens=64)
+    act = np.sqrt((X.astype(np.float64) ** 2).sum(axis=0)).astype(np.float32) ** np.float32(0.5)
+    S = vnm.vnm_ria_scores(_dev(W), _dev(act))
+    c = vnm.vnm_prune_compress_scored(_dev(W), S, layer.V, layer.M, want_mask=True)
+    torch.cuda.synchronize()
+    S_ref = orc.importance_ria(W, act)
+    assert np.array_equal(S.cpu().numpy().view(np.uint32), S_ref.view(np.uint32))
+    _check_compressed_scored(c, W, S_ref, layer.V, layer.M)

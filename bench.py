@@ -33,7 +33,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama2_7b", choices=["llama2_7b", "deit_small", "deit_base", "single"])
+    ap.add_argument("--workload", default="llama2_7b", choices=["llama2_7b", "deit_small", "deit_base", "single", "sweep"],
+                    help="sweep: times vnm_spmm and vnm_prune_compress against the dense fp16 GEMM over the "
+                         "V x M x tokens grid on the two large Llama shapes and runs the (V, M) selection on it")
     ap.add_argument("--V", type=int, default=None)
     ap.add_argument("--M", type=int, default=None)
     ap.add_argument("--tokens", type=int, default=None)
@@ -55,6 +57,62 @@ def get_layers(args):
     if args.workload == "deit_base":
         return syn.config_deit_base(args.V or 64, args.M or 8)
     return syn.config_single_gemm()
+
+
+def run_sweep(args):
+    """V x M x tokens sweep (not the default workload): one JSON line with the table and, per token
+    count, the (V, M) the two-phase sifting of Section 4.1 selects for a few speedup thresholds.
+    A point's speedup is dense GEMM time / vnm_spmm time summed over the two layer shapes."""
+    import torch
+    import paper_2410_16135_amd as vnm
+    import synth_inputs as syn
+    dev = torch.device("cuda:0")
+
+    def timed(f, n):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            f()
+        b.record(); torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    layers = syn.config_sweep()
+    rows, cache = [], {}
+    for L in layers:
+        key = (L.out, L.inn)
+        if key not in cache:
+            W, _ = syn.layer_tensors(L, tokens=1)
+            cache[key] = torch.from_numpy(W).to(dev)
+        Wd = cache[key]
+        _, X = syn.layer_tensors(L)
+        Xd = torch.from_numpy(X).to(dev)
+        Y = torch.empty((L.tokens, L.out), dtype=torch.float16, device=dev)
+        c = vnm.vnm_prune_compress(Wd, L.V, L.M)
+        n = max(args.steps, 5)
+        t_sp = timed(lambda: vnm.vnm_spmm(Xd, c, Y=Y), n)
+        t_de = timed(lambda: torch.matmul(Xd, Wd.t(), out=Y), n)
+        t_pr = timed(lambda: vnm.vnm_prune_compress(Wd, L.V, L.M, out=c), 5)
+        rows.append({"layer": L.name.split("_")[0], "out": L.out, "in": L.inn, "V": L.V, "M": L.M, "tokens": L.tokens,
+                     "spmm_ms": round(t_sp, 4), "dense_fp16_ms": round(t_de, 4), "speedup": round(t_de / t_sp, 3),
+                     "prune_compress_ms": round(t_pr, 4)})
+    selection = {}
+    for T in sorted({r["tokens"] for r in rows}):
+        cands = []
+        for V in sorted({r["V"] for r in rows}):
+            for M in sorted({r["M"] for r in rows}):
+                pts = [r for r in rows if r["tokens"] == T and r["V"] == V and r["M"] == M]
+                cands.append((V, M, sum(r["dense_fp16_ms"] for r in pts) / sum(r["spmm_ms"] for r in pts)))
+        sel = {}
+        for s_thr in (1.0, 1.25, 1.5, 2.0, 2.5):
+            i = vnm.vnm_select_vm(cands, s_thr)
+            sel[str(s_thr)] = None if i < 0 else {"V": cands[i][0], "M": cands[i][1], "speedup": round(cands[i][2], 3),
+                                                  "ln_K": vnm.vnm_mask_diversity_log(cands[i][0], cands[i][1])}
+        selection[str(T)] = sel
+    print(json.dumps({"metric": "V:N:M SpMM speedup vs dense fp16 GEMM, sweep", "unit": "x", "n_gpus": 1,
+                      "data": "synthetic", "config": {"workload": "sweep V x M x tokens on 11008x4096 and 4096x11008"},
+                      "points": rows, "selected_vm_by_threshold": selection}))
 
 
 def L0_is_default(layers):
@@ -102,6 +160,9 @@ def main():
     import paper_2410_16135_amd as vnm
     import synth_inputs as syn
 
+    if args.workload == "sweep":
+        run_sweep(args)
+        return
     dev = torch.device("cuda:0")
     layers = get_layers(args)
     # ---- resident inputs and preallocated outputs

@@ -177,6 +177,21 @@ int vnm_decompress(const void* values, const void* meta, const void* colidx,
                    int64_t out, int64_t in, int V, int N, int M,
                    void* W_out, int64_t ldw, void* stream);
 
+/*
+ * V and M selection (Section 4.1, Eq. 4-5 and Appendix B).  Host only.
+ * vnm_mask_diversity_log: ln K(V, M) = (ln C(M,4) + V ln C(4,N)) / (V M), the per-weight logarithm
+ * of the mask diversity; for one network a larger K means a larger mask diversity whatever the
+ * layer shapes.  N must be 2, 4 <= M <= 255.
+ * vnm_select_vm: the two-phase sifting.  Candidates i = 0..n-1 are (V[i], M[i]) with measured
+ * speedup[i] over the dense model; those with speedup >= threshold qualify; for every V only its
+ * smallest qualifying M stays; of the rest the one of largest K is selected (ties: higher speedup,
+ * then smaller V, then lower i).  *selected = its index, or -1 if none qualifies.  M = 4 stands for
+ * plain 2:4 (K does not depend on V then).
+ */
+int vnm_mask_diversity_log(int V, int N, int M, double* ln_k);
+int vnm_select_vm(const int* V, const int* M, const double* speedup, int n, double threshold,
+                  int* selected);
+
 const char* vnm_status_string(int status);
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char* vnm_last_hip_error(void);

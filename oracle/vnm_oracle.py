@@ -12,6 +12,8 @@ Everything here follows the paper's own wording of the method:
   2:4 inside the four surviving columns of every row).
 * Section 3, Eq. 1: the RIA importance score (importance_ria) as an
   alternative to |w|; prune() and compress() take any score matrix.
+* Section 4.1 (Eq. 4-5, Appendix B): mask diversity and the two-phase (V, M)
+  sifting (mask_diversity_log, select_vm).
 * Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
   input dimension is a multiple of M and the output dimension a multiple of V.
 * Appendix A: the compressed triple -- the compact kept values (A_n), the four
@@ -297,3 +299,32 @@ def max_normalised_error(Y, Y_ref) -> float:
     if denom == 0.0:
         return float(np.max(np.abs(np.asarray(Y, dtype=np.float64)))) if Y_ref.size else 0.0
     return float(np.max(np.abs(np.asarray(Y, dtype=np.float64) - Y_ref)) / denom)
+
+
+# ---------------------------------------------------------------- V and M selection (Section 4.1)
+
+def mask_diversity_log(V: int, M: int, N: int = N_KEPT) -> float:
+    """ln K(V, M) of Eq. 5 / Appendix B: K = [C(M,4) * C(4,N)^V] ** (1 / (V*M)).
+
+    The mask diversity of a layer [m x n] is K ** (m*n); for one network the order of the mask
+    diversities of two (V, M) choices is the order of their K."""
+    import math
+    return (math.log(math.comb(M, COLS_KEPT)) + V * math.log(math.comb(COLS_KEPT, N))) / (V * M)
+
+
+def select_vm(candidates, threshold: float):
+    """Two-phase sifting of Section 4.1.  candidates: sequence of (V, M, speedup).  Returns the
+    index of the selected candidate or -1.  Phase 1: among the candidates with speedup >=
+    threshold keep, for every V, the smallest M.  Phase 2: largest K(V, M); ties (the paper is
+    silent) go to the higher speedup, then the smaller V, then the earlier entry."""
+    ok = [i for i, (_, _, s) in enumerate(candidates) if s >= threshold]
+    kept = []
+    for i in ok:
+        V, M, _ = candidates[i]
+        if all(not (candidates[j][0] == V and (candidates[j][1] < M or (candidates[j][1] == M and j < i)))
+               for j in ok if j != i):
+            kept.append(i)
+    if not kept:
+        return -1
+    return min(kept, key=lambda i: (-mask_diversity_log(candidates[i][0], candidates[i][1]),
+                                    -candidates[i][2], candidates[i][0], i))

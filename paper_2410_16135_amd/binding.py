@@ -55,6 +55,11 @@ def load_library():
     lib.vnm_ria_scores.restype = ci
     lib.vnm_prune_compress_scored.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.vnm_prune_compress_scored.restype = ci
+    lib.vnm_mask_diversity_log.argtypes = [ci, ci, ci, ctypes.POINTER(ctypes.c_double)]
+    lib.vnm_mask_diversity_log.restype = ci
+    lib.vnm_select_vm.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_double), ci,
+                                  ctypes.c_double, ctypes.POINTER(ci)]
+    lib.vnm_select_vm.restype = ci
     lib.vnm_stage_x_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(i64)]
     lib.vnm_stage_x_bytes.restype = ci
     lib.vnm_spmm_scratch_bytes.argtypes = [i64, i64, ctypes.POINTER(i64)]
@@ -270,3 +275,20 @@ def vnm_decompress(c: Compressed, N: int = 2, W_out=None):
                                          c.M, _ptr(W_out), W_out.stride(0), _stream(c.values)),
            "vnm_decompress")
     return W_out
+
+
+def vnm_mask_diversity_log(V: int, M: int, N: int = 2) -> float:
+    k = ctypes.c_double(0.0)
+    _check(load_library().vnm_mask_diversity_log(V, N, M, ctypes.byref(k)), "vnm_mask_diversity_log")
+    return k.value
+
+
+def vnm_select_vm(candidates, threshold: float) -> int:
+    """candidates: sequence of (V, M, speedup); returns the index of the selected one or -1."""
+    n = len(candidates)
+    V = (ctypes.c_int * max(n, 1))(*[int(c[0]) for c in candidates])
+    M = (ctypes.c_int * max(n, 1))(*[int(c[1]) for c in candidates])
+    sp = (ctypes.c_double * max(n, 1))(*[float(c[2]) for c in candidates])
+    sel = ctypes.c_int(-1)
+    _check(load_library().vnm_select_vm(V, M, sp, n, float(threshold), ctypes.byref(sel)), "vnm_select_vm")
+    return sel.value

@@ -184,13 +184,15 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def run_step(record):
+    def run_step(record, full):
+        """One step.  record: list that receives (layer, events) or None.  full: events around every
+        call (the untimed breakdown pass); otherwise only around the product kernel."""
         for (L, Wd, Xd, c, Y, Wout) in state:
             e = [ev() for _ in range(5)] if record is not None else None
             if not args.spmm_only:
-                if e: e[0].record()
+                if e and full: e[0].record()
                 vnm.vnm_prune_compress(Wd, L.V, L.M, out=c)
-            if e: e[1].record()
+            if e and full: e[1].record()
             # vnm_spmm = staging pass + product kernel; issued as its two halves so that the
             # product kernel can be timed on its own (same kernels, same work as vnm_spmm)
             vnm.vnm_stage_x(Xd, L.M, staged=staged)
@@ -199,38 +201,48 @@ def main():
             if e: e[2].record()
             if not args.spmm_only:
                 vnm.vnm_decompress(c, W_out=Wout)
-                if e: e[3].record()
+                if e and full: e[3].record()
             if e: record.append((L, e))
 
     for _ in range(args.warmup):
-        run_step(None)
+        run_step(None, False)
     torch.cuda.synchronize()
     records = []
     t_begin = ev(); t_end = ev()
     wall0 = time.perf_counter()
     t_begin.record()
     for _ in range(args.steps):
-        run_step(records)
+        run_step(records, False)
     t_end.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     step_ms = t_begin.elapsed_time(t_end) / args.steps
+    # breakdown pass (after the timed region, not part of `value`): events around every call
+    records_full = []
+    for _ in range(max(3, min(args.steps, 10))):
+        run_step(records_full, True)
+    torch.cuda.synchronize()
 
-    # ---- per-kernel times from the events inside the timed region
+    # ---- product-kernel times from the events inside the timed region; the other calls' times
+    # from the breakdown pass
     per = {}
     for (L, e) in records:
         d = per.setdefault(L.name, {"prune_compress_ms": 0.0, "spmm_ms": 0.0, "decompress_ms": 0.0,
-                                    "stage_ms": 0.0, "product_ms": 0.0, "n": 0})
+                                    "stage_ms": 0.0, "product_ms": 0.0, "n": 0, "nf": 0})
+        d["product_ms"] += e[4].elapsed_time(e[2])
+        d["n"] += 1
+    for (L, e) in records_full:
+        d = per[L.name]
         if not args.spmm_only:
             d["prune_compress_ms"] += e[0].elapsed_time(e[1])
             d["decompress_ms"] += e[2].elapsed_time(e[3])
-        d["spmm_ms"] += e[1].elapsed_time(e[2])
         d["stage_ms"] += e[1].elapsed_time(e[4])
-        d["product_ms"] += e[4].elapsed_time(e[2])
-        d["n"] += 1
+        d["nf"] += 1
     for d in per.values():
-        for k in ("prune_compress_ms", "spmm_ms", "decompress_ms", "stage_ms", "product_ms"):
-            d[k] /= d["n"]
+        d["product_ms"] /= d["n"]
+        for k in ("prune_compress_ms", "decompress_ms", "stage_ms"):
+            d[k] /= d["nf"]
+        d["spmm_ms"] = d["stage_ms"] + d["product_ms"]
 
     # ---- dense fp16 baseline (same shapes, fp16 in / fp32 accumulate / fp16 out)
     dense_ms = {}

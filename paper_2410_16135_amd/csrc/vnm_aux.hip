@@ -49,29 +49,29 @@ int launch_decompress(const void* values, const void* meta, const void* colidx, 
 // last real one get value 0 and positions (0, 1).
 __global__ void __launch_bounds__(256)
 pack_kernel(const unsigned short* __restrict__ values, const unsigned char* __restrict__ meta,
-            const unsigned char* __restrict__ colidx, int V, int SB, int M, int64_t R, int64_t B, int64_t S,
+            const unsigned char* __restrict__ colidx, int V, int M, int64_t R, int64_t Rp, int64_t B, int64_t S,
             unsigned short* __restrict__ pa, unsigned short* __restrict__ pidx,
             unsigned char* __restrict__ pcol) {
-  // R, V here are those of the packed copy (row blocks of VP = packed_v(V) rows); SB of them share
-  // one row block of the pattern and its column indices
-  const int tiles = V / 32;
+  // Rp packed row blocks of 64 rows (2 tiles of 32); R row blocks of V rows in the pattern
+  const int NT = V == 32 ? 2 : 1;                 // column tables per packed row block
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t total = R * S * tiles * 64;
+  const int64_t total = Rp * S * 2 * 64;
   if (gid < total) {
     const int lane = (int)(gid & 63);
     int64_t rest = gid >> 6;
-    const int at = (int)(rest % tiles); rest /= tiles;
+    const int at = (int)(rest & 1); rest >>= 1;
     const int64_t s = rest % S;
-    const int64_t r = rest / S;
+    const int64_t rp = rest / S;
     const int i = lane & 31, h = lane >> 5;
-    const int64_t row = r * V + at * 32 + i;
+    const int64_t row = rp * 64 + at * 32 + i;
+    const bool row_ok = row < R * V;              // rows beyond the padded matrix: value 0, positions (0, 1)
     unsigned short v[8];
     unsigned idx = 0;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int64_t b = s * 8 + 4 * h + g;
       unsigned pair = 0, nib = 4;                                  // (0, 1)
-      if (b < B) {
+      if (b < B && row_ok) {
         pair = *(const unsigned*)(values + row * 2 * B + 2 * b);
         const unsigned byte = meta[row * ((B + 1) / 2) + (b >> 1)];
         nib = (b & 1) ? (byte >> 4) : (byte & 15u);
@@ -83,25 +83,28 @@ pack_kernel(const unsigned short* __restrict__ values, const unsigned char* __re
     uint4 q;
     q.x = v[0] | ((unsigned)v[1] << 16); q.y = v[2] | ((unsigned)v[3] << 16);
     q.z = v[4] | ((unsigned)v[5] << 16); q.w = v[6] | ((unsigned)v[7] << 16);
-    *(uint4*)(pa + (((r * S + s) * tiles + at) * 64 + lane) * 8) = q;
-    pidx[((r * S + s) * 64 + lane) * tiles + at] = (unsigned short)idx;
+    *(uint4*)(pa + (((rp * S + s) * 2 + at) * 64 + lane) * 8) = q;
+    pidx[((rp * S + s) * 64 + lane) * 2 + at] = (unsigned short)idx;
   }
-  // pcol: one thread per (r, s, h, kq): the four staged-row offsets of the lane class (h, kq).
+  // pcol: one thread per (rp, s, h, kq, table): the four staged-row offsets of the lane class (h, kq).
   // Load m of the B operand covers block blk(m, h) = 4*(m/2) + 2*h + (m%2) of the step.
-  const int64_t ncol_items = R * S * 8;
+  const int64_t ncol_items = Rp * S * 8 * NT;
   if (gid < ncol_items) {
-    const int kq = (int)(gid & 3), h = (int)((gid >> 2) & 1);
-    const int64_t rs = gid >> 3;
-    const int64_t s = rs % S, r = rs / S;
+    const int t = (int)(gid % NT);
+    const int64_t g2 = gid / NT;
+    const int kq = (int)(g2 & 3), h = (int)((g2 >> 2) & 1);
+    const int64_t rs = g2 >> 3;
+    const int64_t s = rs % S, rp = rs / S;
+    const int64_t r = (rp * 64 + t * 32) / V;     // row block of the pattern that owns this table
     unsigned o = 0;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
       const int blk = 4 * (m >> 1) + 2 * h + (m & 1);
       const int64_t b = s * 8 + blk;
-      const unsigned c = (b < B) ? colidx[((r / SB) * B + b) * 4 + kq] : (unsigned)kq;
+      const unsigned c = (b < B && r < R) ? colidx[(r * B + b) * 4 + kq] : (unsigned)kq;
       o |= (unsigned)(blk * M + c) << (8 * m);
     }
-    *(unsigned*)(pcol + gid * 4) = o;
+    ((unsigned*)pcol)[gid] = o;
   }
 }
 
@@ -109,12 +112,12 @@ int launch_pack(const void* values, const void* meta, const void* colidx, const 
                 void* packed, hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   if (pl.total == 0) return VNM_ERR_UNSUPPORTED;
-  const int VP = packed_v(d.V), SB = d.V / VP;
-  const int64_t total = d.R * SB * d.S * (VP / 32) * 64;
+  const int64_t Rp = packed_row_blocks(d);
+  const int64_t total = Rp * d.S * 2 * 64;
   char* p = (char*)packed;
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                      (const unsigned short*)values, (const unsigned char*)meta,
-                     (const unsigned char*)colidx, VP, SB, d.M, d.R * SB, d.B, d.S,
+                     (const unsigned char*)colidx, d.V, d.M, d.R, Rp, d.B, d.S,
                      (unsigned short*)(p + pl.pa_off), (unsigned short*)(p + pl.pidx_off),
                      (unsigned char*)(p + pl.pcol_off));
   hipError_t e = hipGetLastError();

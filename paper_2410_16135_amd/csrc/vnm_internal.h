@@ -36,21 +36,24 @@ inline Dims make_dims(int64_t out, int64_t in, int V, int M) {
 
 inline bool has_packed(int V, int M) { return (V == 32 || V == 64 || V == 128) && M <= 16; }
 
-// The matrix-core copy is organised in row blocks of at most 64 rows: a 128-row block of the pattern
-// is stored as two 64-row blocks that carry the same column table, so one product kernel serves both.
-inline int packed_v(int V) { return V == 128 ? 64 : V; }
+// The matrix-core copy is organised in row blocks of 64 rows (two 32-row tiles) whatever V is: a
+// 128-row block of the pattern is stored as two 64-row blocks that carry the same column table, and
+// two 32-row blocks of the pattern share one 64-row block that carries both their column tables
+// (table t belongs to tile t).  One product kernel then serves V = 32, 64 and 128.
+constexpr int kPackedRows = 64;
+inline int64_t packed_row_blocks(const Dims& d) { return (d.out_pad + kPackedRows - 1) / kPackedRows; }
+inline int packed_tables(int V) { return V == 32 ? 2 : 1; }
 
 inline PackedLayout packed_layout(const Dims& d) {
   PackedLayout p{0, 0, 0, 0};
   if (!has_packed(d.V, d.M)) return p;
   auto up = [](int64_t x) { return (x + 255) / 256 * 256; };
-  const int64_t tiles = packed_v(d.V) / 32;
-  const int64_t Rp = d.R * (d.V / packed_v(d.V));
+  const int64_t Rp = packed_row_blocks(d);
   p.pa_off = 0;
-  p.pidx_off = up(Rp * d.S * tiles * 64 * 8 * 2);
-  p.pcol_off = p.pidx_off + up(Rp * d.S * 64 * tiles * 2);
+  p.pidx_off = up(Rp * d.S * 2 * 64 * 8 * 2);
+  p.pcol_off = p.pidx_off + up(Rp * d.S * 64 * 2 * 2);
   // + 8 KiB that the product kernel's look-ahead loads may read (never use) past the last row block
-  p.total = p.pcol_off + up(Rp * d.S * 32) + 8192;
+  p.total = p.pcol_off + up(Rp * d.S * 32 * packed_tables(d.V)) + 8192;
   return p;
 }
 

@@ -128,8 +128,9 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   // [2e+1 : 2e].  The matrix-core copy is stored from here; the canonical values and metadata of
   // the four blocks are parked in the tile, over the 4M elements they came from, for phase 3.
   const int tiles = V / 32;
-  const int ptiles = tiles > 2 ? 2 : tiles;          // 32-row tiles per packed row block
-  const int SB = tiles / ptiles;                     // packed row blocks per row block of the pattern
+  // matrix-core copy: 64-row blocks of two 32-row tiles; tile `at` of this row block is tile
+  // number r * tiles + at of the whole matrix
+  const bool odd_tail = a.pa && tiles == 1 && (a.R & 1) && r == a.R - 1;   // V = 32: a last 64-row block with one real tile
   for (int item = tid; item < nks * 64; item += 256) {
     const int ks = item >> 6, lane = item & 63;
     const int i = lane & 31, h = lane >> 5;
@@ -151,9 +152,8 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
       }
       ixs[at] = (unsigned short)ix;
       if (a.pa) {
-        // packed row block (at most 64 rows) and 32-row tile inside it
-        const int64_t rp = r * SB + at / ptiles;
-        a.pa[(((rp * a.S + s_begin + ks) * ptiles) + at % ptiles) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
+        const int64_t gt = r * tiles + at;
+        a.pa[(((gt >> 1) * a.S + s_begin + ks) * 2 + (gt & 1)) * 64 + lane] = make_uint4(q[0], q[1], q[2], q[3]);
       }
       // 8-byte aligned: blk0 is a multiple of 4
       *(uint2*)trow = make_uint2(q[0], q[1]);
@@ -161,11 +161,17 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
       trow[8] = (unsigned short)ix;
     }
     if (a.pa) {
-      if (ptiles == 1) a.pidx[(r * a.S + s_begin + ks) * 64 + lane] = ixs[0];
-      else
-        for (int sb = 0; sb < SB; ++sb)
-          *(unsigned*)(a.pidx + (((r * SB + sb) * a.S + s_begin + ks) * 64 + lane) * 2) =
+      if (tiles == 1) {
+        a.pidx[(((r >> 1) * a.S + s_begin + ks) * 64 + lane) * 2 + (r & 1)] = ixs[0];
+        if (odd_tail) {           // the missing second tile: values 0, positions (0, 1)
+          a.pa[(((r >> 1) * a.S + s_begin + ks) * 2 + 1) * 64 + lane] = make_uint4(0, 0, 0, 0);
+          a.pidx[(((r >> 1) * a.S + s_begin + ks) * 64 + lane) * 2 + 1] = (unsigned short)0x4444u;
+        }
+      } else {
+        for (int sb = 0; sb < tiles / 2; ++sb)
+          *(unsigned*)(a.pidx + (((r * (tiles / 2) + sb) * a.S + s_begin + ks) * 64 + lane) * 2) =
               (unsigned)ixs[2 * sb] | ((unsigned)ixs[2 * sb + 1] << 16);
+      }
     }
   }
   __syncthreads();
@@ -213,7 +219,17 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         const unsigned c = (keep[ks * 8 + blk] >> (8 * kq)) & 255u;
         o |= (unsigned)(blk * M + c) << (8 * m);
       }
-      for (int sb = 0; sb < SB; ++sb) a.pcol[((r * SB + sb) * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
+      if (tiles == 1) {
+        // two column tables per 64-row block, table r & 1 is this row block's
+        a.pcol[((((r >> 1) * a.S + s_begin + ks) * 8 + h * 4 + kq) << 1) + (r & 1)] = o;
+        if (odd_tail) {
+          unsigned od = 0;
+          for (int m = 0; m < 4; ++m) od |= (unsigned)((4 * (m >> 1) + 2 * h + (m & 1)) * M + kq) << (8 * m);
+          a.pcol[((((r >> 1) * a.S + s_begin + ks) * 8 + h * 4 + kq) << 1) + 1] = od;
+        }
+      } else {
+        for (int sb = 0; sb < tiles / 2; ++sb) a.pcol[((r * (tiles / 2) + sb) * a.S + s_begin + ks) * 8 + h * 4 + kq] = o;
+      }
     }
   }
   // phase 4: optional dense 0-1 mask, from the positions parked in the tile

@@ -3,7 +3,7 @@
 //
 // With so few tokens the product is a stream of the compressed weight through the matrix cores at
 // HBM rate; what matters is that every byte of it is requested early and read once.  One workgroup
-// owns one row block of the packed copy (32 or 64 rows) and the whole K range; its 8 waves take the
+// owns one 64-row block of the packed copy and the whole K range; its 8 waves take the
 // K steps round-robin, each into private accumulators, and add them up through LDS at the end, so
 // no partial products leave the chip.  K is walked in phases of P steps: the A operands and the
 // slice of X of phase p+1 are requested before phase p is multiplied and are parked (X: in a
@@ -38,9 +38,11 @@ struct SkinnyArgs {
   int npz; int64_t z_stride;
 };
 
-// AT: 32-row tiles per packed row block; TT: token rows held in LDS (16 or 32)
-template <int AT, int TT>
+// DUAL: the 64-row block carries one column table per 32-row tile (V = 32 patterns) instead of one
+// for both; TT: token rows held in LDS (16 or 32)
+template <bool DUAL, int TT>
 __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const SkinnyArgs a) {
+  constexpr int AT = 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -84,7 +86,7 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
     }
   };
 
-  struct AOp { uint4 w[AT]; unsigned idx; uint4 pc; };
+  struct AOp { uint4 w[AT]; unsigned idx; uint4 pc, pc2; };
   const int hB = lane >> 5;
   auto load_a = [&](AOp (&o)[kSkSPW], int p) {
 #pragma unroll
@@ -94,9 +96,9 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
         const int64_t rs = r * S + s;
 #pragma unroll
         for (int t = 0; t < AT; ++t) o[i].w[t] = a.pa[(rs * AT + t) * 64 + lane];
-        if (AT == 1) o[i].idx = a.pidx[rs * 64 + lane];
-        else o[i].idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
-        o[i].pc = a.pcol[rs * 2 + hB];
+        o[i].idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
+        if (DUAL) { o[i].pc = a.pcol[rs * 4 + hB * 2]; o[i].pc2 = a.pcol[rs * 4 + hB * 2 + 1]; }
+        else o[i].pc = a.pcol[rs * 2 + hB];
       }
     }
   };
@@ -114,22 +116,34 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
       const int64_t s = (int64_t)p * P + wave + kSkWaves * i;
       if (i < spw && s < S) {
         const unsigned char* row = smem + (size_t)buf * bufB + (size_t)tokl * pitch + (size_t)(wave + kSkWaves * i) * 16 * M;
-        const unsigned pc[4] = {o[i].pc.x, o[i].pc.y, o[i].pc.z, o[i].pc.w};
-        sk_u8 bw;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-          // element 4m + kq of the B operand: kept column kq of column block blk(m, h)
-          unsigned v[4];
-#pragma unroll
-          for (int kq = 0; kq < 4; ++kq) v[kq] = *(const unsigned short*)(row + 2 * ((pc[kq] >> (8 * m)) & 255u));
-          bw[2 * m] = v[0] | (v[1] << 16);
-          bw[2 * m + 1] = v[2] | (v[3] << 16);
+        // column tables as [kq] -> 4 packed row offsets (byte m = load m); DUAL interleaves the
+        // two tables: (kq 0 table 0, kq 0 table 1, kq 1 table 0, ...)
+        unsigned pc[2][4];
+        if (DUAL) {
+          pc[0][0] = o[i].pc.x; pc[1][0] = o[i].pc.y; pc[0][1] = o[i].pc.z; pc[1][1] = o[i].pc.w;
+          pc[0][2] = o[i].pc2.x; pc[1][2] = o[i].pc2.y; pc[0][3] = o[i].pc2.z; pc[1][3] = o[i].pc2.w;
+        } else {
+          pc[0][0] = o[i].pc.x; pc[0][1] = o[i].pc.y; pc[0][2] = o[i].pc.z; pc[0][3] = o[i].pc.w;
         }
-        const sk_h16 bv = __builtin_bit_cast(sk_h16, bw);
         const int ix = (int)o[i].idx;
-        acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[0]), bv, acc[0], ix, 0, 0);
-        if (AT == 2)
-          acc[AT - 1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[AT - 1]), bv, acc[AT - 1], ix, 0, 1);
+#pragma unroll
+        for (int t = 0; t < (DUAL ? 2 : 1); ++t) {
+          sk_u8 bw;
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            // element 4m + kq of the B operand: kept column kq of column block blk(m, h)
+            unsigned v[4];
+#pragma unroll
+            for (int kq = 0; kq < 4; ++kq) v[kq] = *(const unsigned short*)(row + 2 * ((pc[t][kq] >> (8 * m)) & 255u));
+            bw[2 * m] = v[0] | (v[1] << 16);
+            bw[2 * m + 1] = v[2] | (v[3] << 16);
+          }
+          const sk_h16 bv = __builtin_bit_cast(sk_h16, bw);
+          if (!DUAL || t == 0)
+            acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[0]), bv, acc[0], ix, 0, 0);
+          if (!DUAL || t == 1)
+            acc[1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o[i].w[1]), bv, acc[1], ix, 0, 1);
+        }
       }
     }
   };
@@ -178,13 +192,13 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
 
 int64_t skinny_max_tokens() { return 32; }
 
-template <int AT, int TT>
+template <bool DUAL, int TT>
 static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t st) {
   const size_t bufB = ((size_t)TT * (a.P * 16 * a.M + 4) + 15) & ~(size_t)15;
   size_t lds = 2 * bufB;
-  const size_t red = (size_t)kSkWaves * TT * (AT * 32 + 1) * 4;
+  const size_t red = (size_t)kSkWaves * TT * (2 * 32 + 1) * 4;
   if (red > lds) lds = red;
-  auto kern = spmm_skinny_kernel<AT, TT>;
+  auto kern = spmm_skinny_kernel<DUAL, TT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -202,8 +216,8 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
                        hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
-  const int VP = packed_v(d.V);
-  const int64_t R = d.R * (d.V / VP);
+  const bool dual = packed_tables(d.V) == 2;
+  const int64_t R = packed_row_blocks(d);
   if (R > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
   SkinnyArgs a;
   a.X = (const unsigned short*)X; a.T = T; a.ldx = ldx; a.in = d.in;
@@ -238,8 +252,8 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   }
   if (KS > 1) { a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out; }
   int rc = VNM_ERR_UNSUPPORTED;
-  if (VP == 64) rc = TT == 16 ? launch_skinny_cfg<2, 16>(a, R, KS, st) : launch_skinny_cfg<2, 32>(a, R, KS, st);
-  if (VP == 32) rc = TT == 16 ? launch_skinny_cfg<1, 16>(a, R, KS, st) : launch_skinny_cfg<1, 32>(a, R, KS, st);
+  if (!dual) rc = TT == 16 ? launch_skinny_cfg<false, 16>(a, R, KS, st) : launch_skinny_cfg<false, 32>(a, R, KS, st);
+  else rc = TT == 16 ? launch_skinny_cfg<true, 16>(a, R, KS, st) : launch_skinny_cfg<true, 32>(a, R, KS, st);
   if (rc != VNM_OK || KS == 1) return rc;
   return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);
 }

@@ -19,8 +19,8 @@
 //     (kept values in lane order + 2-bit positions) comes straight from the packed copy in global
 //     memory, one 16-byte load per lane and tile; accumulators stay in registers for the whole K
 //     loop.
-//   * For V = 64 the steady-state K loop is written in assembly (see below); other V use a
-//     compiler-scheduled loop that drains memory every step.
+//   * The K loop is written in assembly (see below), in two variants: one column table per
+//     64-row block (V = 64, 128) or one per 32-row tile (V = 32).
 #include <type_traits>
 #include <stdlib.h>
 #include "vnm_internal.h"
@@ -30,32 +30,14 @@ namespace vnm {
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
-typedef short s4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 #define VNM_LDS(T) __attribute__((address_space(3))) T*
 #define VNM_GLB(T) __attribute__((address_space(1))) T*
 
-// ds_read_b64_tr_b16: 16 lanes x 8 bytes in, transposed out: lanes 4j..4j+3 of a 16-lane group
-// address row j (16 consecutive fp16 of it), and lane i receives element i of each of the 4 rows.
-// Issued through inline assembly on purpose: the compiler must not see these as LDS reads, or it
-// would drain every outstanding asynchronous global->LDS copy (vmcnt(0)) in front of each of them.
-// The matching lgkmcnt waits are therefore written by hand (lds_wait below), tied to the
-// destination registers so that no use can be scheduled ahead of the wait.
-template <int OFF>
-__device__ __forceinline__ h4 lds_read_tr(unsigned byte_addr) {
-  h4 v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(byte_addr), "n"(OFF) : "memory");
-  return v;
-}
-template <int N>
-__device__ __forceinline__ void lds_wait(h4& a, h4& b, h4& c, h4& d) {
-  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt_imm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
+// ds_read_b64_tr_b16 (used by the loop below): 16 lanes x 8 bytes in, transposed out: lanes
+// 4j..4j+3 of a 16-lane group address row j (16 consecutive fp16 of it), and lane i receives
+// element i of each of the 4 rows.
 
 // ---------------------------------------------------------------------------------------------
 // Steady-state K loop for V = 64 (2 A tiles x 4 B tiles per wave), written in assembly.
@@ -229,6 +211,128 @@ __device__ __forceinline__ void wait_vmcnt_imm() {
         "v252", "v253",                                                                           \
         "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89")
 
+// ---------------------------------------------------------------------------------------------
+// The same loop for packed row blocks that carry two column tables (V = 32: the two 32-row tiles of
+// a wave belong to different row blocks of the pattern and gather different columns).  Every MFMA
+// then has a B operand of its own: 8 operands of 4 reads per step, kept in a ring of four 8-register
+// slots; operand i + 3 is requested right after MFMA i into the slot MFMA i - 1 has just used, so at
+// every use the 8 reads of the two following operands may still be in flight (lgkmcnt(8)).
+// Registers: v178 v179 scratch, v[180:183] row addresses of table 0, v[184:187] of table 1,
+// slots v[188:195] v[196:203] v[204:211] v[212:219], A sets {values tile 0, values tile 1, index
+// word, column tables 0 and 1} with even-aligned tuples: {v[220:223] v[224:227] v230 v[228:229]},
+// {v[232:235] v[236:239] v242 v[240:241]}, {v[244:247] v[248:251] v243 v[252:253]}.
+#define VNM_D_READ4(OFF, X, A0)                                                                   \
+  "ds_read_b64_tr_b16 v[" #X ":" #X "+1], v[" #A0 "] offset:" #OFF "\n"                           \
+  "ds_read_b64_tr_b16 v[" #X "+2:" #X "+3], v[" #A0 "+1] offset:" #OFF "\n"                       \
+  "ds_read_b64_tr_b16 v[" #X "+4:" #X "+5], v[" #A0 "+2] offset:" #OFF "\n"                       \
+  "ds_read_b64_tr_b16 v[" #X "+6:" #X "+7], v[" #A0 "+3] offset:" #OFF "\n"
+#define VNM_D_A_ADVANCE                                                        \
+  "s_add_u32 s80, s80, 2048\n s_addc_u32 s81, s81, 0\n"                        \
+  "s_add_u32 s82, s82, 256\n s_addc_u32 s83, s83, 0\n"                         \
+  "s_add_u32 s84, s84, 64\n s_addc_u32 s85, s85, 0\n"
+#define VNM_D_LOAD_A(W0, W1, IDX, PC)                                          \
+  "global_load_dwordx4 v[" W0 "], %[voff16], s[80:81]\n"                       \
+  "global_load_dwordx4 v[" W1 "], %[voff16], s[80:81] offset:1024\n"           \
+  "global_load_dword v" IDX ", %[voffi], s[82:83]\n"                           \
+  "global_load_dwordx2 v[" PC "], %[voffp], s[84:85]\n"                        \
+  VNM_D_A_ADVANCE
+#define VNM_D_ADDR1(PC, A0, A1, A2, A3)                                                           \
+      "v_and_b32 v179, 0xff, v" PC "\n"                                                           \
+      "v_mad_u32_u24 v" #A0 ", v179, %[pitch], v178\n"                                            \
+      "v_bfe_u32 v179, v" PC ", 8, 8\n"                                                           \
+      "v_mad_u32_u24 v" #A1 ", v179, %[pitch], v178\n"                                            \
+      "v_bfe_u32 v179, v" PC ", 16, 8\n"                                                          \
+      "v_mad_u32_u24 v" #A2 ", v179, %[pitch], v178\n"                                            \
+      "v_lshrrev_b32 v179, 24, v" PC "\n"                                                         \
+      "v_mad_u32_u24 v" #A3 ", v179, %[pitch], v178\n"
+#define VNM_D_ADDR(PC0, PC1)                                                                      \
+      "v_add_u32 v178, %[rd], %[vtok]\n"                                                          \
+      VNM_D_ADDR1(PC0, 180, 181, 182, 183) VNM_D_ADDR1(PC1, 184, 185, 186, 187)
+#define VNM_D_W "s_waitcnt lgkmcnt(8)\n s_nop 0\n"
+// CUR set = (CW0, CW1, CIDX); NPC0/NPC1 = column tables of the next step's set; LOAD set receives A(s+2)
+#define VNM_D_STEP(CW0, CW1, CIDX, NPC0, NPC1, LW0, LW1, LIDX, LPC, COPY_A, COPY_B, VMWSTR)        \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a00], v[" CW0 "], v[188:195], v" CIDX "\n"                     \
+      "global_load_dwordx4 v[" LW0 "], %[voff16], s[80:81]\n"                                     \
+      VNM_D_READ4(64, 212, 184)                                                                   \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a10], v[" CW1 "], v[196:203], v" CIDX " abid:1\n"              \
+      "global_load_dwordx4 v[" LW1 "], %[voff16], s[80:81] offset:1024\n"                         \
+      VNM_D_READ4(128, 188, 180)                                                                  \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a01], v[" CW0 "], v[204:211], v" CIDX "\n"                     \
+      "global_load_dword v" LIDX ", %[voffi], s[82:83]\n"                                         \
+      VNM_D_READ4(128, 196, 184)                                                                  \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a11], v[" CW1 "], v[212:219], v" CIDX " abid:1\n"              \
+      "global_load_dwordx2 v[" LPC "], %[voffp], s[84:85]\n"                                      \
+      VNM_D_READ4(192, 204, 180)                                                                  \
+      VNM_D_A_ADVANCE                                                                             \
+      "s_add_u32 %[rd], %[rd], %[img]\n s_cmp_eq_u32 %[rd], %[lend]\n s_cselect_b32 %[rd], %[lbeg], %[rd]\n" \
+      "s_waitcnt vmcnt(" VMWSTR ")\n"                                                             \
+      "s_barrier\n"                                                                               \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a02], v[" CW0 "], v[188:195], v" CIDX "\n"                     \
+      VNM_D_READ4(192, 212, 184)                                                                  \
+      COPY_A                                                                                      \
+      VNM_D_ADDR(NPC0, NPC1)                                                                      \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a12], v[" CW1 "], v[196:203], v" CIDX " abid:1\n"              \
+      VNM_D_READ4(0, 188, 180)                                                                    \
+      COPY_B                                                                                      \
+      "s_add_u32 %[wr], %[wr], %[img]\n s_cmp_eq_u32 %[wr], %[lend]\n s_cselect_b32 %[wr], %[lbeg], %[wr]\n" \
+      "s_add_u32 s86, s86, %[img]\n s_addc_u32 s87, s87, 0\n"                                     \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a03], v[" CW0 "], v[204:211], v" CIDX "\n"                     \
+      VNM_D_READ4(0, 196, 184)                                                                    \
+      VNM_D_W                                                                                     \
+      "v_smfmac_f32_32x32x32_f16 %[a13], v[" CW1 "], v[212:219], v" CIDX " abid:1\n"              \
+      VNM_D_READ4(64, 204, 180)                                                                   \
+      "s_sub_u32 %[n], %[n], 1\n"                                                                 \
+      "s_cmp_eq_u32 %[n], 0\n"                                                                    \
+      "s_cbranch_scc1 9f\n"
+
+#define VNM_ASM_LOOP_D(COPY_A, COPY_B, VMWSTR)                                                    \
+  asm volatile(                                                                                   \
+      "s_mov_b32 s80, %[pa_lo]\n s_mov_b32 s81, %[pa_hi]\n"                                       \
+      "s_mov_b32 s82, %[pi_lo]\n s_mov_b32 s83, %[pi_hi]\n"                                       \
+      "s_mov_b32 s84, %[pc_lo]\n s_mov_b32 s85, %[pc_hi]\n"                                       \
+      "s_mov_b32 s86, %[xs_lo]\n s_mov_b32 s87, %[xs_hi]\n"                                       \
+      VNM_D_LOAD_A("220:223", "224:227", "230", "228:229")                                        \
+      VNM_D_LOAD_A("232:235", "236:239", "242", "240:241")                                        \
+      "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
+      "s_barrier\n"                                                                               \
+      VNM_D_ADDR("228", "229")                                                                    \
+      VNM_D_READ4(0, 188, 180)                                                                    \
+      VNM_D_READ4(0, 196, 184)                                                                    \
+      VNM_D_READ4(64, 204, 180)                                                                   \
+      "1:\n"                                                                                      \
+      VNM_D_STEP("220:223", "224:227", "230", "240", "241", "244:247", "248:251", "243", "252:253", COPY_A, COPY_B, VMWSTR) \
+      VNM_D_STEP("232:235", "236:239", "242", "252", "253", "220:223", "224:227", "230", "228:229", COPY_A, COPY_B, VMWSTR) \
+      VNM_D_STEP("244:247", "248:251", "243", "228", "229", "232:235", "236:239", "242", "240:241", COPY_A, COPY_B, VMWSTR) \
+      "s_branch 1b\n"                                                                             \
+      "9:\n"                                                                                      \
+      "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
+      "s_barrier\n"                                                                               \
+      : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
+        [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
+        [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                    \
+      : [pa_lo] "s"(l_pa_lo), [pa_hi] "s"(l_pa_hi), [pi_lo] "s"(l_pi_lo), [pi_hi] "s"(l_pi_hi),   \
+        [pc_lo] "s"(l_pc_lo), [pc_hi] "s"(l_pc_hi), [xs_lo] "s"(l_xs_lo), [xs_hi] "s"(l_xs_hi),   \
+        [voff16] "v"(l_voff16), [voffi] "v"(l_voffi), [voffp] "v"(l_voffp), [vtok] "v"(l_vtok),   \
+        [woff] "s"(l_woff), [clamp] "s"(l_clamp), [pitch] "s"(l_pitch), [img] "s"(l_img),         \
+        [lbeg] "s"(l_lbeg), [lend] "s"(l_lend)                                                    \
+      : "memory", "scc", "m0",                                                                    \
+        "v178", "v179", "v180", "v181", "v182", "v183", "v184", "v185",                           \
+        "v186", "v187", "v188", "v189", "v190", "v191",                                           \
+        "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", \
+        "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", \
+        "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", \
+        "v228", "v229", "v230", "v231", "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", \
+        "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", \
+        "v252", "v253",                                                                           \
+        "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89")
+
 struct SpmmArgs {
   const unsigned char* Xs; int64_t T;
   const uint4* pa; const unsigned short* pidx; const unsigned* pcol;
@@ -247,15 +351,15 @@ struct SpmmArgs {
 // One K step = 8 column blocks = 8*M raw input columns = 32 compacted K = one staged image.
 // NCW: wave-wide 1 KiB copies per wave and image (V = 64 assembly loop; 0 elsewhere).
 // NBUF: depth of the LDS image ring.
-template <int V, int TW, int WR, int WT, int NCW, int NBUF>
+// DUAL: the packed row blocks carry two column tables (V = 32 patterns), assembly loop only.
+template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL>
 __global__ void __launch_bounds__(64 * WR * WT)
 spmm_smfmac_kernel(const SpmmArgs a) {
   constexpr int AT = V / 32, BT = TW / 32, NW = WR * WT;
   static_assert(WT * TW == kTokTile, "a workgroup spans one staged token tile");
   static_assert(BT <= 4 && AT <= 4, "tiling assumed by the step body");
   constexpr int P = kImagePitch;
-  constexpr int NI = (AT + 1) / 2;
-  constexpr bool kAsmLoop = (V == 64 && TW == 128 && NCW > 0);
+  static_assert(V == 64 && TW == 128 && NCW > 0, "the K loop exists as the assembly loop for 64-row blocks only");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -298,78 +402,11 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     }
   };
 
-  // A operand of one K step as it sits in registers
-  struct AOp { uint4 w[AT]; unsigned idx[NI]; unsigned pc4; };
-  const uint4* pa_w = a.pa + rs0 * AT * 64 + lane;
-  const unsigned* pidx_w = (const unsigned*)a.pidx;      // AT >= 2: AT/2 dwords per lane and step
-  const unsigned* pcol_w = a.pcol + rs0 * 8 + hB * 4 + kq;
-  auto load_a = [&](AOp& o, int64_t s) {
-#pragma unroll
-    for (int i = 0; i < AT; ++i) o.w[i] = pa_w[(s * AT + i) * 64];
-    if (AT == 1) o.idx[0] = a.pidx[(rs0 + s) * 64 + lane];
-    else {
-#pragma unroll
-      for (int i = 0; i < AT / 2; ++i) o.idx[i] = pidx_w[((rs0 + s) * 64 + lane) * (AT / 2) + i];
-    }
-    o.pc4 = pcol_w[s * 8];
-  };
-
-  // Compiler-scheduled K step (all V; for V = 64 only the first and last few steps).  Drains all
-  // memory traffic before its barrier: simple and always correct, but it serialises the copies.
-  AOp cur, nxt;
-  auto step = [&](int64_t s) {
-    const int slot = (int)(s % NBUF);
-    if (s + 1 < S) load_a(nxt, s + 1);
-    if (s + NBUF - 1 < S) copy_image(s + NBUF - 1, (int)((s + NBUF - 1) % NBUF));
-    unsigned addr[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-      addr[m] = lds0 + slot * img + ((cur.pc4 >> (8 * m)) & 255u) * P + tokoff;
-    h8 av[AT];
-#pragma unroll
-    for (int i = 0; i < AT; ++i) av[i] = __builtin_bit_cast(h8, cur.w[i]);
-    const int idx0 = (int)cur.idx[0];
-    const int idx1 = (int)cur.idx[NI - 1];
-    h4 b[BT][4];
-    // all B reads of the step first (LDS returns in order), then per tile: wait, multiply
-#define VNM_RD(j) { b[j][0] = lds_read_tr<(j) * 64>(addr[0]); b[j][1] = lds_read_tr<(j) * 64>(addr[1]); \
-                    b[j][2] = lds_read_tr<(j) * 64>(addr[2]); b[j][3] = lds_read_tr<(j) * 64>(addr[3]); }
-    VNM_RD(0)
-    if (BT > 1) VNM_RD(1 % BT)
-    if (BT > 2) VNM_RD(2 % BT)
-    if (BT > 3) VNM_RD(3 % BT)
-#undef VNM_RD
-    __builtin_amdgcn_sched_barrier(0);
-#define VNM_MM(j) {                                                                              \
-      lds_wait<4 * (BT - 1 - (j))>(b[j][0], b[j][1], b[j][2], b[j][3]);                          \
-      h16 bv;                                                                                    \
-      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                            \
-        bv[e] = b[j][0][e]; bv[4 + e] = b[j][1][e]; bv[8 + e] = b[j][2][e]; bv[12 + e] = b[j][3][e]; } \
-      _Pragma("unroll") for (int i = 0; i < AT; ++i) {                                           \
-        const int ix = (i / 2 == 0) ? idx0 : idx1;                                               \
-        if (i & 1) acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], ix, 0, 1); \
-        else acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av[i], bv, acc[i][j], ix, 0, 0); } \
-      __builtin_amdgcn_sched_barrier(0); }
-    VNM_MM(0)
-    if (BT > 1) VNM_MM(1 % BT)
-    if (BT > 2) VNM_MM(2 % BT)
-    if (BT > 3) VNM_MM(3 % BT)
-#undef VNM_MM
-    wait_vmcnt_imm<0>();
-    __builtin_amdgcn_s_barrier();
-    cur = nxt;
-  };
-
   // prologue: the first NBUF-1 images (the assembly loop waits for them together with its first
   // A operands, one memory latency instead of two)
   for (int k = 0; k < NBUF - 1 && k < S; ++k) copy_image(k, k);
-  if constexpr (!kAsmLoop) {
-    wait_vmcnt_imm<0>();
-    __builtin_amdgcn_s_barrier();
-  }
 
-  int64_t s = 0;
-  if constexpr (kAsmLoop) {
+  {
     // All S steps run in the assembly loop.  Every step requests the image NBUF-1 steps ahead and
     // the A operand 2 steps ahead without looking at S: near the end these requests reach past the
     // tile's images and past the row block's operands, into the next tile / row block or into the
@@ -378,13 +415,13 @@ spmm_smfmac_kernel(const SpmmArgs a) {
     {
       const uint64_t pa_p = (uint64_t)(a.pa + rs0 * AT * 64);
       const uint64_t pi_p = (uint64_t)(a.pidx + rs0 * 64 * AT);
-      const uint64_t pc_p = (uint64_t)(a.pcol + rs0 * 8);
+      const uint64_t pc_p = (uint64_t)(a.pcol + rs0 * (DUAL ? 16 : 8));
       const uint64_t xs_p = (uint64_t)(xs_tile + (int64_t)(NBUF - 1) * img);
       unsigned l_pa_lo = __builtin_amdgcn_readfirstlane((unsigned)pa_p), l_pa_hi = __builtin_amdgcn_readfirstlane((unsigned)(pa_p >> 32));
       unsigned l_pi_lo = __builtin_amdgcn_readfirstlane((unsigned)pi_p), l_pi_hi = __builtin_amdgcn_readfirstlane((unsigned)(pi_p >> 32));
       unsigned l_pc_lo = __builtin_amdgcn_readfirstlane((unsigned)pc_p), l_pc_hi = __builtin_amdgcn_readfirstlane((unsigned)(pc_p >> 32));
       unsigned l_xs_lo = __builtin_amdgcn_readfirstlane((unsigned)xs_p), l_xs_hi = __builtin_amdgcn_readfirstlane((unsigned)(xs_p >> 32));
-      unsigned l_voff16 = lane * 16, l_voffi = lane * 4, l_voffp = (hB * 4 + kq) * 4, l_vtok = tokoff;
+      unsigned l_voff16 = lane * 16, l_voffi = lane * 4, l_voffp = (hB * 4 + kq) * (DUAL ? 8 : 4), l_vtok = tokoff;
       unsigned l_woff = wave * 1024, l_clamp = (n_ci - 1) * 1024, l_pitch = P, l_img = img;
       unsigned l_lbeg = __builtin_amdgcn_readfirstlane(lds0), l_lend = l_lbeg + NBUF * img;
       unsigned l_rd = l_lbeg, l_wr = l_lbeg + (NBUF - 1) * img, l_tci;
@@ -394,19 +431,20 @@ spmm_smfmac_kernel(const SpmmArgs a) {
       // its start and, with a ring of 4, the NCW copies issued after the previous step's barrier
       // (with a ring of 3 those copies are image s+1 itself and must have landed)
 #define VNM_GO(W, N, VM3, VM4)                                                    \
-      if constexpr (NW == W && NCW == N) {                                       \
+      if constexpr (NW == W && NCW == N && !DUAL) {                              \
         if constexpr (NBUF == 4) VNM_ASM_LOOP_V64(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM4);  \
         else VNM_ASM_LOOP_V64(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM3);         \
+      }                                                                          \
+      if constexpr (NW == W && NCW == N && DUAL) {                               \
+        if constexpr (NBUF == 4) VNM_ASM_LOOP_D(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM4);    \
+        else VNM_ASM_LOOP_D(VNM_C##W##_##N##A, VNM_C##W##_##N##B, VM3);           \
       }
       VNM_GO(4, 3, "4", "7") VNM_GO(4, 4, "4", "8") VNM_GO(4, 5, "4", "9") VNM_GO(4, 6, "4", "10")
       VNM_GO(4, 7, "4", "11") VNM_GO(4, 8, "4", "12") VNM_GO(4, 9, "4", "13") VNM_GO(4, 10, "4", "14")
       VNM_GO(8, 2, "4", "6") VNM_GO(8, 3, "4", "7") VNM_GO(8, 4, "4", "8") VNM_GO(8, 5, "4", "9")
 #undef VNM_GO
-      s = n_steady;
     }
   }
-  if (s < S) { load_a(cur, s); }
-  for (; s < S; ++s) step(s);
 
   // ---- epilogue.  A lane holds, per (A tile, B tile, jq), 4 consecutive output channels of one
   // token -- 8 bytes of fp16 -- so storing straight from the accumulators would scatter 8-byte
@@ -486,12 +524,12 @@ bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d) {
   return has_packed(d.V, d.M) && d.in % 8 == 0 && ldx % 8 == 0 && ((uintptr_t)X & 15) == 0;
 }
 
-template <int V, int TW, int WR, int WT, int NCW, int NBUF>
+template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL>
 static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
   size_t lds = (size_t)NBUF * a.image_bytes;
   const size_t ep = (size_t)WR * WT * TW * (V * 2 + 8);     // epilogue transposition, per wave [TW][V] fp16
   if (ep > lds) lds = ep;
-  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF>;
+  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF, DUAL>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -508,29 +546,29 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
 
 // V = 64: pick the assembly loop by workgroup size (4 or 8 row blocks), by copies per wave
 // (NCW = ceil(image KiB / waves)) and by ring depth.
-template <int NBUF>
+template <int NBUF, bool DUAL>
 static int launch_v64_w4(const SpmmArgs& a, hipStream_t st) {
   const int ncw = (a.image_bytes / 1024 + 3) / 4;
   switch (ncw) {
-    case 3: return launch_cfg<64, 128, 4, 1, 3, NBUF>(a, st);
-    case 4: return launch_cfg<64, 128, 4, 1, 4, NBUF>(a, st);
-    case 5: return launch_cfg<64, 128, 4, 1, 5, NBUF>(a, st);
-    case 6: return launch_cfg<64, 128, 4, 1, 6, NBUF>(a, st);
-    case 7: return launch_cfg<64, 128, 4, 1, 7, NBUF>(a, st);
-    case 8: return launch_cfg<64, 128, 4, 1, 8, NBUF>(a, st);
-    case 9: return launch_cfg<64, 128, 4, 1, 9, NBUF>(a, st);
-    case 10: return launch_cfg<64, 128, 4, 1, 10, NBUF>(a, st);
+    case 3: return launch_cfg<64, 128, 4, 1, 3, NBUF, DUAL>(a, st);
+    case 4: return launch_cfg<64, 128, 4, 1, 4, NBUF, DUAL>(a, st);
+    case 5: return launch_cfg<64, 128, 4, 1, 5, NBUF, DUAL>(a, st);
+    case 6: return launch_cfg<64, 128, 4, 1, 6, NBUF, DUAL>(a, st);
+    case 7: return launch_cfg<64, 128, 4, 1, 7, NBUF, DUAL>(a, st);
+    case 8: return launch_cfg<64, 128, 4, 1, 8, NBUF, DUAL>(a, st);
+    case 9: return launch_cfg<64, 128, 4, 1, 9, NBUF, DUAL>(a, st);
+    case 10: return launch_cfg<64, 128, 4, 1, 10, NBUF, DUAL>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }
-template <int NBUF>
+template <int NBUF, bool DUAL>
 static int launch_v64_w8(const SpmmArgs& a, hipStream_t st) {
   const int ncw = (a.image_bytes / 1024 + 7) / 8;
   switch (ncw) {
-    case 2: return launch_cfg<64, 128, 8, 1, 2, NBUF>(a, st);
-    case 3: return launch_cfg<64, 128, 8, 1, 3, NBUF>(a, st);
-    case 4: return launch_cfg<64, 128, 8, 1, 4, NBUF>(a, st);
-    case 5: return launch_cfg<64, 128, 8, 1, 5, NBUF>(a, st);
+    case 2: return launch_cfg<64, 128, 8, 1, 2, NBUF, DUAL>(a, st);
+    case 3: return launch_cfg<64, 128, 8, 1, 3, NBUF, DUAL>(a, st);
+    case 4: return launch_cfg<64, 128, 8, 1, 4, NBUF, DUAL>(a, st);
+    case 5: return launch_cfg<64, 128, 8, 1, 5, NBUF, DUAL>(a, st);
   }
   return VNM_ERR_UNSUPPORTED;
 }
@@ -575,8 +613,8 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.pa = (const uint4*)(p + pl.pa_off);
   a.pidx = (const unsigned short*)(p + pl.pidx_off);
   a.pcol = (const unsigned*)(p + pl.pcol_off);
-  const int VP = packed_v(d.V);
-  a.out = d.out; a.R = d.R * (d.V / VP); a.S = d.S; a.M = d.M;     // row blocks of the packed copy
+  const bool dual = packed_tables(d.V) == 2;
+  a.out = d.out; a.R = packed_row_blocks(d); a.S = d.S; a.M = d.M;  // 64-row blocks of the packed copy
   a.image_bytes = (int)image_bytes(d.M);
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.ks_steps = d.S; a.z_stride = 0;
@@ -592,7 +630,7 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   // writes an fp32 partial product to the scratch, a second kernel adds them up.
   int KS = 1;
   const int64_t base = tiles * ((a.R + 3) / 4);
-  if (scratch && T <= kSplitKMaxTokens && base < 192 && VP == 64) {
+  if (scratch && T <= kSplitKMaxTokens && base < 192) {
     int64_t ks = (200 + base / 2) / base;                            // about 200 workgroups measured best
     if (ks > 16) ks = 16;
     if (ks > d.S / 4) ks = d.S / 4;                                   // at least 4 K steps each
@@ -610,12 +648,13 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.wide_store = (a.y_fp32 == 0) && (a.ldy % 8 == 0) && (((uintptr_t)a.Y & 15) == 0);
   a.vec_store = (a.ldy % 4 == 0) && (((uintptr_t)a.Y & (a.y_fp32 == 0 ? 7 : 15)) == 0);
   int rc = VNM_ERR_UNSUPPORTED;
-  switch (VP) {
-    case 32: rc = launch_cfg<32, 128, 8, 1, 0, 3>(a, st); break;
-    case 64:
-      if (wide) rc = 4 * (size_t)a.image_bytes <= 150 * 1024 ? launch_v64_w8<4>(a, st) : launch_v64_w8<3>(a, st);
-      else rc = deep ? launch_v64_w4<4>(a, st) : launch_v64_w4<3>(a, st);
-      break;
+  const bool ring4 = 4 * (size_t)a.image_bytes <= 150 * 1024;
+  if (!dual) {
+    if (wide) rc = ring4 ? launch_v64_w8<4, false>(a, st) : launch_v64_w8<3, false>(a, st);
+    else rc = deep ? launch_v64_w4<4, false>(a, st) : launch_v64_w4<3, false>(a, st);
+  } else {
+    if (wide) rc = ring4 ? launch_v64_w8<4, true>(a, st) : launch_v64_w8<3, true>(a, st);
+    else rc = deep ? launch_v64_w4<4, true>(a, st) : launch_v64_w4<3, true>(a, st);
   }
   if (rc != VNM_OK || KS == 1) return rc;
   return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);

@@ -382,3 +382,33 @@ def test_ria_prune_llama_shaped_layer_full_size():
     S_ref = orc.importance_ria(W, act)
     assert np.array_equal(S.cpu().numpy().view(np.uint32), S_ref.view(np.uint32))
     _check_compressed_scored(c, W, S_ref, layer.V, layer.M)
+
+
+@pytest.mark.parametrize("out,inn,V,M", [(96, 160, 32, 5), (160, 256, 32, 8), (200, 128, 64, 6), (130, 320, 128, 7),
+                                         (32, 64, 32, 4)])
+def test_pack_from_triple_equals_fused_copy(out, inn, V, M):
+    """vnm_pack on the canonical triple builds the same matrix-core copy as the fused pruning kernel
+    (byte for byte, up to the trailing slack that no one writes), for 32-row patterns -- two row
+    blocks per 64-row packed block, also with an odd number of them --, 64 and 128; and the product
+    from either copy, many-token and few-token kernel, matches the oracle."""
+    rng = np.random.default_rng(out + inn + V)
+    W = _rand_w(rng, out, inn, "normal")
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    c2 = vnm.Compressed(c.values, c.meta, c.colidx, None, out, inn, V, M, c.mask)
+    vnm.vnm_pack(c2)
+    torch.cuda.synchronize()
+    # sections of the copy (each starts on a 256-byte boundary; the gaps and the slack are unwritten)
+    up = lambda x: (x + 255) // 256 * 256
+    Rp, S = (-(-out // V) * V + 63) // 64, -(-(-(-inn // M)) // 8)
+    sizes = [Rp * S * 2048, Rp * S * 256, Rp * S * 32 * (2 if V == 32 else 1)]
+    off = 0
+    for nbytes in sizes:
+        assert torch.equal(c.packed[off:off + nbytes], c2.packed[off:off + nbytes])
+        off += up(nbytes)
+    assert off + 8192 == c.packed.numel()
+    Wm = orc.masked_dense(W, c.mask.cpu().numpy())
+    for T in (7, 150):
+        X = rng.standard_normal((T, inn)).astype(np.float16)
+        Y = vnm.vnm_spmm(_dev(X), c2, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+        torch.cuda.synchronize()
+        assert orc.max_normalised_error(Y.cpu().numpy(), orc.matmul_ref(X, Wm)) <= TOL

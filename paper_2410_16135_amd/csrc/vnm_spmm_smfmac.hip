@@ -620,10 +620,14 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   a.ks_steps = d.S; a.z_stride = 0;
   if ((T + kTokTile - 1) / kTokTile > 0x7FFFFFFF || (a.R + 1) / 2 > 65535) return VNM_ERR_UNSUPPORTED;
   const bool deep = 2 * 4 * (size_t)a.image_bytes <= 150 * 1024;
-  // 8 row blocks per workgroup halve the image traffic per flop; worth it when there are enough
-  // row blocks to keep every CU busy with one such workgroup
+  // 8 row blocks per workgroup (one per CU) halve the image traffic per flop, 4 (two per CU) give
+  // twice as many workgroups.  Pick by the number of rounds the grid needs on the 256 CUs: a round
+  // costs the K loop (about 15 % slower per step with 4) plus a fixed prologue and store of about 12
+  // K steps' worth, which dominates when K is short.
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
-  bool wide = a.R >= 8 && tiles * ((a.R + 7) / 8) >= 200;
+  const int64_t rounds8 = (tiles * ((a.R + 7) / 8) + 255) / 256, rounds4 = (tiles * ((a.R + 3) / 4) + 511) / 512;
+  const double cost8 = (double)rounds8 * ((double)d.S + 12.0), cost4 = (double)rounds4 * (1.15 * (double)d.S + 12.0);
+  bool wide = a.R >= 8 && cost8 <= cost4;
   { const char* e = getenv("VNM_SPMM_WG"); if (e) wide = atoi(e) == 8; }
   // Few tokens: too few (token tile, row group) pairs to occupy the 256 CUs, and the job is to
   // stream the compressed weight at HBM rate.  Split K over up to 16 workgroups per pair; each

@@ -1,12 +1,29 @@
 // C ABI of libvnm: argument validation on the host, then dispatch to the kernel launchers.
 #include <string.h>
 #include <stdio.h>
+#include <mutex>
+#include <set>
+#include <utility>
 #include "vnm_internal.h"
 
 namespace vnm {
 static thread_local char g_hip_error[256] = "";
 void set_hip_error(hipError_t e, const char* where) {
   snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", where, hipGetErrorString(e));
+}
+
+int allow_big_lds(const void* kernel, const char* what) {
+  static std::mutex mu;
+  static std::set<std::pair<const void*, int>> done;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_hip_error(e, "hipGetDevice"); return VNM_ERR_HIP; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (done.count({kernel, dev})) return VNM_OK;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) { set_hip_error(e, what); return VNM_ERR_HIP; }
+  done.insert({kernel, dev});
+  return VNM_OK;
 }
 }  // namespace vnm
 

@@ -64,6 +64,9 @@ inline int64_t image_bytes(int M) { return ((int64_t)8 * M * kImagePitch + 1023)
 int64_t staged_bytes(int64_t T, const Dims& d);
 
 void set_hip_error(hipError_t e, const char* where);
+// Raises a kernel's dynamic-LDS limit to the 160 KiB of a gfx950 CU, once per (kernel, device); thread-safe.
+// Returns a vnm_status.
+int allow_big_lds(const void* kernel, const char* what);
 
 // launchers (each returns a vnm_status)
 int launch_prune_compress(const void* W, int64_t ldw, const Dims& d, void* values, void* meta,

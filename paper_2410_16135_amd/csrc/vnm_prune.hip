@@ -136,13 +136,7 @@ int launch_prune_compress(const void* W, int64_t ldw, const Dims& d, void* value
   const size_t pitch = (size_t)NB * d.M;
   size_t lds = (((size_t)d.V * pitch * 2 + 15) & ~(size_t)15) + pitch * 8 + (size_t)NB * 4 + (size_t)d.V * NB;
   if (lds > 160 * 1024) return VNM_ERR_UNSUPPORTED;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)prune_compress_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(prune_compress)"); return VNM_ERR_HIP; }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds((const void*)prune_compress_kernel, "hipFuncSetAttribute(prune_compress)")) return rc_lds;
   dim3 grid((unsigned)((d.B + NB - 1) / NB), (unsigned)d.R);
   hipLaunchKernelGGL(prune_compress_kernel, grid, dim3(256), lds, st, (const unsigned short*)W, ldw,
                      d.out, d.in, d.V, d.M, d.B, NB, (unsigned short*)values, (unsigned char*)meta,

@@ -6,7 +6,6 @@
 // vnm_prune.hip: column L1 norms are exact integer sums of the fp16 magnitudes, ties go to the
 // lower index.
 #include "vnm_internal.h"
-#include <cstdlib>
 
 namespace vnm {
 
@@ -276,7 +275,6 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
   a.W = (const unsigned short*)W; a.ldw = ldw; a.out = d.out; a.in = d.in; a.V = d.V; a.M = d.M;
   a.R = d.R; a.B = d.B; a.S = d.S;
   a.KSW = prune_fast_ksw(d);
-  if (const char* e = getenv("VNM_PRUNE_KSW")) { const int k = atoi(e); if (k >= 1 && k <= 8) a.KSW = k < a.KSW ? k : a.KSW; }
   const int chunks = a.KSW * d.M;
   a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
   a.values = (unsigned short*)values; a.meta = (unsigned char*)meta; a.colidx = (unsigned char*)colidx;
@@ -288,12 +286,7 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
     a.pa = (uint4*)(p + pl.pa_off); a.pidx = (unsigned short*)(p + pl.pidx_off); a.pcol = (unsigned*)(p + pl.pcol_off);
   }
   const size_t lds = prune_fast_lds(d.V, d.M, a.KSW);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)prune_pack_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(prune_pack)"); return VNM_ERR_HIP; }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds((const void*)prune_pack_kernel, "hipFuncSetAttribute(prune_pack)")) return rc_lds;
   // row blocks along x: workgroups that share a span of columns' cache lines with their
   // neighbours in y sit R apart in launch order
   dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
@@ -390,17 +383,11 @@ int launch_decompress_fast(const void* values, const void* meta, const void* col
   a.values = (const unsigned short*)values; a.meta = (const unsigned char*)meta; a.colidx = (const unsigned char*)colidx;
   a.out = d.out; a.in = d.in; a.B = d.B; a.S = d.S; a.V = d.V; a.M = d.M;
   a.KSW = prune_fast_ksw(d);
-  if (const char* e = getenv("VNM_DECOMP_KSW")) { const int k = atoi(e); if (k >= 1 && k <= 8) a.KSW = k < a.KSW ? k : a.KSW; }
   const int chunks = a.KSW * d.M;
   a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
   a.Wd = (unsigned short*)W_out; a.ldw = ldw;
   const size_t lds = (size_t)d.V * (a.KSW * 8 * d.M + 8) * 2 + (size_t)a.KSW * 8 * 4;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)decompress_fast_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(decompress_fast)"); return VNM_ERR_HIP; }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds((const void*)decompress_fast_kernel, "hipFuncSetAttribute(decompress_fast)")) return rc_lds;
   dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
   hipLaunchKernelGGL(decompress_fast_kernel, grid, dim3(256), lds, st, a);
   hipError_t e = hipGetLastError();

@@ -13,7 +13,6 @@
 // (conflict-free: lanes differ in the row).  That is 16 LDS instructions per matrix instruction
 // pair, far below what the streaming rate needs; the transposing staged layout of the many-token
 // kernel would cost a second launch.
-#include <cstdlib>
 #include "vnm_internal.h"
 
 namespace vnm {
@@ -199,12 +198,7 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
   const size_t red = (size_t)kSkWaves * TT * (2 * 32 + 1) * 4;
   if (red > lds) lds = red;
   auto kern = spmm_skinny_kernel<DUAL, TT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(spmm_skinny)"); return VNM_ERR_HIP; }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny)")) return rc_lds;
   hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS), dim3(64 * kSkWaves), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_kernel"); return VNM_ERR_HIP; }
@@ -244,7 +238,6 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
     if (ks > 16) ks = 16;
     if (ks > nph) ks = nph;
     while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
-    if (const char* e = getenv("VNM_SKINNY_KS")) { const int k = atoi(e); if (k >= 1 && k <= ks) ks = k; }
     if (ks > 1) {
       a.npz = (int)((nph + ks - 1) / ks);
       KS = (nph + a.npz - 1) / a.npz;

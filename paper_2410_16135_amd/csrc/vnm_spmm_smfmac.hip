@@ -22,7 +22,6 @@
 //   * The K loop is written in assembly (see below), in two variants: one column table per
 //     64-row block (V = 64, 128) or one per 32-row tile (V = 32).
 #include <type_traits>
-#include <stdlib.h>
 #include "vnm_internal.h"
 
 namespace vnm {
@@ -530,12 +529,7 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
   const size_t ep = (size_t)WR * WT * TW * (V * 2 + 8);     // epilogue transposition, per wave [TW][V] fp16
   if (ep > lds) lds = ep;
   auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF, DUAL>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(spmm_smfmac)"); return VNM_ERR_HIP; }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_smfmac)")) return rc_lds;
   dim3 grid((unsigned)((a.T + kTokTile - 1) / kTokTile), (unsigned)((a.R + WR - 1) / WR),
             (unsigned)((a.S + a.ks_steps - 1) / a.ks_steps));
   hipLaunchKernelGGL(kern, grid, dim3(64 * WR * WT), lds, st, a);
@@ -628,7 +622,6 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   const int64_t rounds8 = (tiles * ((a.R + 7) / 8) + 255) / 256, rounds4 = (tiles * ((a.R + 3) / 4) + 511) / 512;
   const double cost8 = (double)rounds8 * ((double)d.S + 12.0), cost4 = (double)rounds4 * (1.15 * (double)d.S + 12.0);
   bool wide = a.R >= 8 && cost8 <= cost4;
-  { const char* e = getenv("VNM_SPMM_WG"); if (e) wide = atoi(e) == 8; }
   // Few tokens: too few (token tile, row group) pairs to occupy the 256 CUs, and the job is to
   // stream the compressed weight at HBM rate.  Split K over up to 16 workgroups per pair; each
   // writes an fp32 partial product to the scratch, a second kernel adds them up.
@@ -639,7 +632,6 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
     if (ks > 16) ks = 16;
     if (ks > d.S / 4) ks = d.S / 4;                                   // at least 4 K steps each
     while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
-    if (const char* e = getenv("VNM_SPMM_KS")) { const int k = atoi(e); if (k >= 1 && k <= 16 && k <= d.S) ks = k; }
     if (ks > 1) {
       a.ks_steps = (d.S + ks - 1) / ks;
       KS = (int)((d.S + a.ks_steps - 1) / a.ks_steps);

@@ -11,7 +11,6 @@
 // per element per group of row blocks -- is what keeps the product kernel's inner loop free of
 // shuffles and of scattered 16-byte loads.
 #include "vnm_internal.h"
-#include <cstdlib>
 
 namespace vnm {
 
@@ -105,18 +104,11 @@ int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* X
   // two sub-chunks per workgroup (one level of read/write overlap measured best) unless that
   // would leave fewer workgroups than CUs
   int64_t n_sub = tiles * subs >= 512 ? 2 : 1;
-  if (const char* e = getenv("VNM_STAGE_NSUB")) { const int k = atoi(e); if (k >= 1 && k <= 64) n_sub = k; }
   const int64_t gy = (subs + n_sub - 1) / n_sub;
   if (tiles > 0x7FFFFFFF || gy > 65535) return VNM_ERR_UNSUPPORTED;
   const size_t lds = (size_t)kTokTile * (KC * d.M * 16 + 4);
-  static bool attr_set = false;
-  if (!attr_set) {
-    for (const void* f : {(const void*)stage_x_kernel<2>, (const void*)stage_x_kernel<4>}) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      if (e != hipSuccess) { set_hip_error(e, "hipFuncSetAttribute(stage_x)"); return VNM_ERR_HIP; }
-    }
-    attr_set = true;
-  }
+  if (int rc_lds = allow_big_lds(KC == 4 ? (const void*)stage_x_kernel<4> : (const void*)stage_x_kernel<2>,
+                                 "hipFuncSetAttribute(stage_x)")) return rc_lds;
   dim3 grid((unsigned)tiles, (unsigned)gy);
   if (KC == 4)
     hipLaunchKernelGGL(stage_x_kernel<4>, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,

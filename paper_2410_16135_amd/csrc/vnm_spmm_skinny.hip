@@ -60,25 +60,31 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
   const int tok_first = tid / CH, ch_first = tid - tok_first * CH;
   const int dtok = 512 / CH, dch = 512 - dtok * CH;
 
+  // All global loads below are unconditional (out-of-range pieces read a valid dummy address and
+  // are zeroed or ignored later): loads under a branch would make the number of outstanding loads
+  // unknown to the compiler, which then drains every one of them before the first use of any.
   uint4 xw[kSkNX];
+  auto x_valid = [&](int tok, int ch, int64_t col0) { return tok < TT && tok < a.T && col0 + ch * 8 < a.in; };
   auto load_x = [&](int p) {
     const int64_t col0 = (int64_t)p * ncolP;
     int tok = tok_first, ch = ch_first;
 #pragma unroll
     for (int i = 0; i < kSkNX; ++i) {
-      xw[i] = make_uint4(0, 0, 0, 0);
-      if (tok < TT && tok < a.T && col0 + ch * 8 < a.in) xw[i] = *(const uint4*)(a.X + tok * a.ldx + col0 + ch * 8);
+      const unsigned short* src = x_valid(tok, ch, col0) ? a.X + tok * a.ldx + col0 + ch * 8 : a.X;
+      xw[i] = *(const uint4*)src;
       ch += dch; tok += dtok;
       if (ch >= CH) { ch -= CH; ++tok; }
     }
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](int buf, int p) {
+    const int64_t col0 = (int64_t)p * ncolP;
     int tok = tok_first, ch = ch_first;
 #pragma unroll
     for (int i = 0; i < kSkNX; ++i) {
       if (tok < TT) {
+        const uint4 v = x_valid(tok, ch, col0) ? xw[i] : make_uint4(0, 0, 0, 0);
         unsigned* d = (unsigned*)(smem + (size_t)buf * bufB + (size_t)tok * pitch + ch * 16);
-        d[0] = xw[i].x; d[1] = xw[i].y; d[2] = xw[i].z; d[3] = xw[i].w;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
       }
       ch += dch; tok += dtok;
       if (ch >= CH) { ch -= CH; ++tok; }
@@ -90,15 +96,15 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
   auto load_a = [&](AOp (&o)[kSkSPW], int p) {
 #pragma unroll
     for (int i = 0; i < kSkSPW; ++i) {
-      const int64_t s = (int64_t)p * P + wave + kSkWaves * i;
-      if (i < spw && s < S) {
-        const int64_t rs = r * S + s;
+      // steps beyond the phase or beyond S re-read the last valid one; compute() skips them
+      int64_t s = (int64_t)p * P + wave + kSkWaves * (i < spw ? i : spw - 1);
+      s = s < S ? s : S - 1;
+      const int64_t rs = r * S + s;
 #pragma unroll
-        for (int t = 0; t < AT; ++t) o[i].w[t] = a.pa[(rs * AT + t) * 64 + lane];
-        o[i].idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
-        if (DUAL) { o[i].pc = a.pcol[rs * 4 + hB * 2]; o[i].pc2 = a.pcol[rs * 4 + hB * 2 + 1]; }
-        else o[i].pc = a.pcol[rs * 2 + hB];
-      }
+      for (int t = 0; t < AT; ++t) o[i].w[t] = a.pa[(rs * AT + t) * 64 + lane];
+      o[i].idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
+      if (DUAL) { o[i].pc = a.pcol[rs * 4 + hB * 2]; o[i].pc2 = a.pcol[rs * 4 + hB * 2 + 1]; }
+      else o[i].pc = a.pcol[rs * 2 + hB];
     }
   };
 
@@ -150,17 +156,17 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
   AOp cur[kSkSPW], nxt[kSkSPW];
   load_x(p_begin);
   load_a(cur, p_begin);
-  store_x(p_begin & 1);
+  store_x(p_begin & 1, p_begin);
   __syncthreads();
   for (int p = p_begin; p < p_end; ++p) {
     const bool more = p + 1 < p_end;
-    if (more) { load_x(p + 1); load_a(nxt, p + 1); }
+    const int pn = more ? p + 1 : p;            // the last phase re-requests itself (unused)
+    load_x(pn);
+    load_a(nxt, pn);
     compute(cur, p & 1, p);
-    if (more) {
-      store_x((p + 1) & 1);
+    if (more) store_x((p + 1) & 1, pn);
 #pragma unroll
-      for (int i = 0; i < kSkSPW; ++i) cur[i] = nxt[i];
-    }
+    for (int i = 0; i < kSkSPW; ++i) cur[i] = nxt[i];
     __syncthreads();
   }
 

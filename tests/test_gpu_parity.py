@@ -412,3 +412,37 @@ def test_pack_from_triple_equals_fused_copy(out, inn, V, M):
         Y = vnm.vnm_spmm(_dev(X), c2, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
         torch.cuda.synchronize()
         assert orc.max_normalised_error(Y.cpu().numpy(), orc.matmul_ref(X, Wm)) <= TOL
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        V = int(rng.choice([16, 32, 64, 128]))
+        M = int(rng.choice([4, 5, 6, 7, 8, 9, 12, 16, 19]))
+        out = int(rng.integers(1, 5) * V + rng.integers(-V + 1, 1)) if rng.random() < 0.5 else int(rng.integers(1, 400))
+        inn = int(rng.integers(1, 60)) * 8 if rng.random() < 0.7 else int(rng.integers(4, 500))
+        T = int(rng.choice([1, 2, 15, 16, 17, 31, 32, 33, 64, 127, 128, 129, 200, 257, 300]))
+        cases.append((max(out, 1), inn, T, V, M))
+    return cases
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", _random_cases(48, 2024))
+def test_random_shapes_whole_path(out, inn, T, V, M):
+    """Seeded random shapes through the whole path with the default dispatch (whatever kernel the
+    library picks: fused or general pruning, few-token, split-K, staged matrix-core or generic
+    product), ragged in every dimension, token counts around every internal boundary."""
+    rng = np.random.default_rng(out * 131 + inn * 17 + T + V + M)
+    W = _rand_w(rng, out, inn, "normal" if (out + inn) % 3 else "ints")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float32)
+    Yh = vnm.vnm_spmm(_dev(X), c, out_dtype=torch.float16)
+    Wd = vnm.vnm_decompress(c)
+    torch.cuda.synchronize()
+    _, _, _, mask = _check_compressed(c, W, V, M)
+    Wm = orc.masked_dense(W, mask)
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint16), Wm.view(np.uint16))
+    Y_ref = orc.matmul_ref(X, Wm)
+    assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
+    assert orc.max_normalised_error(Yh.float().cpu().numpy(), Y_ref) <= TOL

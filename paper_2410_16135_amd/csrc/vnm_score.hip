@@ -21,63 +21,127 @@ __global__ void __launch_bounds__(256) fill_u64_kernel(unsigned long long* p, in
   if (i < n) p[i] = 0ull;
 }
 
-// One workgroup: 64 rows x 256 columns of W.  Thread t owns column t of the tile and adds its 64
-// magnitudes; the row sums of the tile are reduced per wave.  Both go to global memory with 64-bit
-// integer atomics (exact, so the order is immaterial).
+// Column sums: a workgroup covers 512 columns x kSumRows rows.  Thread (c, q) owns 8 adjacent columns
+// (one 16-byte load per row) and the rows q, q + 4, ... of the strip; the four partial sums of a
+// column chunk meet in LDS and go to global memory with 64-bit integer atomics (exact, so the order
+// is immaterial).  `vec` = rows are 16-byte aligned; otherwise 2-byte loads.
+constexpr int kSumRows = 128;
 __global__ void __launch_bounds__(256)
-abs_sums_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, int64_t ldw,
-                unsigned long long* __restrict__ colsum, unsigned long long* __restrict__ rowsum) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int64_t col = (int64_t)blockIdx.x * 256 + tid;
-  const int64_t row0 = (int64_t)blockIdx.y * 64;
-  unsigned long long csum = 0;
-  for (int v = 0; v < 64; ++v) {
-    const int64_t row = row0 + v;
-    if (row >= out) break;                                   // uniform over the workgroup
-    unsigned long long u = 0;
-    if (col < in) u = sc_fp16_units(W[row * ldw + col]);
-    csum += u;
-    // sum over the 64 lanes of the wave
-    unsigned long long r = u;
+abs_colsum_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, int64_t ldw, int vec,
+                  unsigned long long* __restrict__ colsum) {
+  __shared__ unsigned long long part[4][64][8];
+  const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t col = ((int64_t)blockIdx.x * 64 + c) * 8;
+  const int64_t row0 = (int64_t)blockIdx.y * kSumRows;
+  const int nc = col >= in ? 0 : (int)((in - col) < 8 ? (in - col) : 8);
+  unsigned long long acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int64_t row1 = row0 + kSumRows < out ? row0 + kSumRows : out;
+  if (nc > 0)
+    for (int64_t row = row0 + q; row < row1; row += 4) {
+      const unsigned short* p = W + row * ldw + col;
+      if (vec && nc == 8) {
+        const uint4 v = *(const uint4*)p;
+        const unsigned d[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const unsigned lo = __shfl_xor((unsigned)r, o), hi = __shfl_xor((unsigned)(r >> 32), o);
-      r += ((unsigned long long)hi << 32) | lo;
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += sc_fp16_units((unsigned short)(d[e] & 0xFFFFu));
+          acc[2 * e + 1] += sc_fp16_units((unsigned short)(d[e] >> 16));
+        }
+      } else {
+        for (int e = 0; e < nc; ++e) acc[e] += sc_fp16_units(p[e]);
+      }
     }
-    if (lane == 0 && r) atomicAdd(rowsum + row, r);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[q][c][e] = acc[e];
+  __syncthreads();
+  // 512 column sums of the strip, two per thread
+  for (int i = threadIdx.x; i < 512; i += 256) {
+    const int cc = i >> 3, e = i & 7;
+    const int64_t gc = (int64_t)blockIdx.x * 512 + i;
+    const unsigned long long t = part[0][cc][e] + part[1][cc][e] + part[2][cc][e] + part[3][cc][e];
+    if (gc < in && t) atomicAdd(colsum + gc, t);
   }
-  if (col < in && csum) atomicAdd(colsum + col, csum);
 }
 
+// Row sums: one wave per row, lanes stride over the row 8 columns at a time, one reduction at the end.
+__global__ void __launch_bounds__(256)
+abs_rowsum_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, int64_t ldw, int vec,
+                  unsigned long long* __restrict__ rowsum) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= out) return;                                    // uniform over the wave
+  const unsigned short* p = W + row * ldw;
+  unsigned long long acc = 0;
+  for (int64_t c = (int64_t)lane * 8; c < in; c += 512) {
+    if (vec && c + 8 <= in) {
+      const uint4 v = *(const uint4*)(p + c);
+      const unsigned d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        acc += sc_fp16_units((unsigned short)(d[e] & 0xFFFFu)) + sc_fp16_units((unsigned short)(d[e] >> 16));
+    } else {
+      for (int64_t e = c; e < in && e < c + 8; ++e) acc += sc_fp16_units(p[e]);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned lo = __shfl_xor((unsigned)acc, o), hi = __shfl_xor((unsigned)(acc >> 32), o);
+    acc += ((unsigned long long)hi << 32) | lo;
+  }
+  if (lane == 0) rowsum[row] = acc;
+}
+
+// Scores: thread t owns 4 adjacent columns (`vec`: one 8-byte load of W and one 16-byte store of S per
+// row) and walks the rows blockIdx.y, blockIdx.y + gridDim.y, ...
 __global__ void __launch_bounds__(256)
 ria_score_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, int64_t ldw,
                  const unsigned long long* __restrict__ colsum, const unsigned long long* __restrict__ rowsum,
-                 const float* __restrict__ act, float* __restrict__ S, int64_t lds) {
-  const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+                 const float* __restrict__ act, float* __restrict__ S, int64_t lds, int vec) {
+  const int64_t col = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (col >= in) return;
-  const unsigned long long cs = colsum[col];
-  const double cd = (double)cs, ad = (double)act[col];
+  const int nc = (int)((in - col) < 4 ? (in - col) : 4);
+  unsigned long long cs[4] = {0, 0, 0, 0};
+  double cd[4] = {0, 0, 0, 0}, ad[4] = {0, 0, 0, 0};
+  for (int e = 0; e < nc; ++e) { cs[e] = colsum[col + e]; cd[e] = (double)cs[e]; ad[e] = (double)act[col + e]; }
   for (int64_t row = blockIdx.y; row < out; row += gridDim.y) {
     const unsigned long long rs = rowsum[row];
-    const double a = (double)sc_fp16_units(W[row * ldw + col]);
-    const double q_col = cs ? a / cd : 0.0;
-    const double q_row = rs ? a / (double)rs : 0.0;
-    const double sum = q_col + q_row;
-    S[row * lds + col] = (float)(sum * ad);
+    const double rd = (double)rs;
+    unsigned short h[4] = {0, 0, 0, 0};
+    if (vec && nc == 4) {
+      const uint2 v = *(const uint2*)(W + row * ldw + col);
+      h[0] = (unsigned short)(v.x & 0xFFFFu); h[1] = (unsigned short)(v.x >> 16);
+      h[2] = (unsigned short)(v.y & 0xFFFFu); h[3] = (unsigned short)(v.y >> 16);
+    } else {
+      for (int e = 0; e < nc; ++e) h[e] = W[row * ldw + col + e];
+    }
+    float sc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double a = (double)sc_fp16_units(h[e]);
+      const double q_col = cs[e] ? a / cd[e] : 0.0;
+      const double q_row = rs ? a / rd : 0.0;
+      const double sum = q_col + q_row;
+      sc[e] = (float)(sum * ad[e]);
+    }
+    if (vec && nc == 4) *(float4*)(S + row * lds + col) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+    else for (int e = 0; e < nc; ++e) S[row * lds + col + e] = sc[e];
   }
 }
 
 int launch_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act, void* S,
                       int64_t lds, void* workspace, hipStream_t st) {
-  if ((in + 255) / 256 > 0x7FFFFFFF || (out + 63) / 64 > 65535) return VNM_ERR_UNSUPPORTED;
+  if ((out + kSumRows - 1) / kSumRows > 65535 || (out + 3) / 4 > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
   unsigned long long* colsum = (unsigned long long*)workspace;
   unsigned long long* rowsum = colsum + in;
-  const int64_t n = in + out;
-  hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, colsum, n);
-  hipLaunchKernelGGL(abs_sums_kernel, dim3((unsigned)((in + 255) / 256), (unsigned)((out + 63) / 64)), dim3(256), 0,
-                     st, (const unsigned short*)W, out, in, ldw, colsum, rowsum);
-  hipLaunchKernelGGL(ria_score_kernel, dim3((unsigned)((in + 255) / 256), (unsigned)(out < 65535 ? out : 65535)), dim3(256), 0, st,
-                     (const unsigned short*)W, out, in, ldw, colsum, rowsum, (const float*)act, (float*)S, lds);
+  const int vec = (ldw % 8 == 0) && (((uintptr_t)W & 15) == 0);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((in + 255) / 256)), dim3(256), 0, st, colsum, in);
+  hipLaunchKernelGGL(abs_colsum_kernel, dim3((unsigned)((in + 511) / 512), (unsigned)((out + kSumRows - 1) / kSumRows)),
+                     dim3(256), 0, st, (const unsigned short*)W, out, in, ldw, vec, colsum);
+  hipLaunchKernelGGL(abs_rowsum_kernel, dim3((unsigned)((out + 3) / 4)), dim3(256), 0, st, (const unsigned short*)W,
+                     out, in, ldw, vec, rowsum);
+  const int vec_s = (ldw % 4 == 0) && (((uintptr_t)W & 7) == 0) && (lds % 4 == 0) && (((uintptr_t)S & 15) == 0);
+  hipLaunchKernelGGL(ria_score_kernel, dim3((unsigned)((in + 1023) / 1024), (unsigned)(out < 65535 ? out : 65535)), dim3(256), 0, st,
+                     (const unsigned short*)W, out, in, ldw, colsum, rowsum, (const float*)act, (float*)S, lds, vec_s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "ria score kernels"); return VNM_ERR_HIP; }
   return VNM_OK;

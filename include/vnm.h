@@ -148,6 +148,50 @@ int vnm_spmm(const void* X, int64_t T, int64_t ldx,
              void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * vnm_spmm with the steps that Section 4.2 says can be merged into the layer at inference (Eq. 6:
+ * Y = P_o^T W_p P_i^T X, W_p = P_o W P_i the channel-permuted weight that was pruned) and the layer's
+ * bias:
+ *   Y[t, perm_out[o]] = bias[o] + sum_i W'_p[o, i] * X[t, perm_in[i]]
+ * where W'_p is the compressed weight handed in.  Each of the three is optional (NULL):
+ *   bias      dev fp16 [out], in the row order of the compressed weight (a bias travels with its
+ *             row: bias[o] is the layer's bias of output channel perm_out[o]); added in fp32
+ *             before the result is rounded
+ *   perm_in   dev int32 [in], 16-byte aligned: column i of the compressed weight multiplies input
+ *             channel perm_in[i] (P_i[perm_in[i], i] = 1); applied while X is re-laid, X itself is
+ *             not modified
+ *   perm_out  dev int32 [out], 4-byte aligned: row o of the compressed weight produces output
+ *             channel perm_out[o] (P_o[o, perm_out[o]] = 1); applied when Y is stored
+ * Both must be permutations of 0..n-1; the device arrays are not checked, but an entry outside the
+ * range never faults: such an input channel reads as zero, such an output channel is not stored
+ * (if perm_out is not a permutation, the contents of columns of Y that no row maps to are
+ * unspecified).
+ * With perm_in the matrix-core path needs the workspace for every T (for T <= 32 it holds a permuted
+ * copy of X).  vnm_spmm_fused_workspace_bytes (host only) is vnm_spmm_workspace_bytes plus, with
+ * perm_in, room for a permuted copy of X; with only vnm_spmm_workspace_bytes the call still works,
+ * the permutation then costs more time.  The cheapest permutation is none: leave Y in the weight's
+ * row order and fold P_o into the next layer's input permutation (vnm_fold_permutations).
+ * Everything else as vnm_spmm.
+ */
+int vnm_spmm_fused(const void* X, int64_t T, int64_t ldx,
+                   const void* values, const void* meta, const void* colidx, const void* packed,
+                   int64_t out, int64_t in, int V, int N, int M,
+                   const void* bias, const void* perm_in, const void* perm_out,
+                   void* Y, int64_t ldy, int y_dtype, int path,
+                   void* workspace, int64_t workspace_bytes, void* stream);
+int vnm_spmm_fused_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
+                                   int with_perm_in, int64_t* bytes);
+
+/*
+ * Host only (host pointers, int32 [n] each).  Merges the output permutation of one layer into the
+ * input permutation of the layer that consumes its output (Section 4.2: the permutations can be
+ * fused with the preceding layer): if the first layer is run without perm_out, its output Z holds
+ * Z[:, o] = Y[:, perm_out_prev[o]], and the next layer must read
+ *   folded[i] = inverse(perm_out_prev)[perm_in_next[i]]
+ * instead of perm_in_next[i].  VNM_ERR_SHAPE if either input is not a permutation of 0..n-1.
+ */
+int vnm_fold_permutations(const void* perm_out_prev, const void* perm_in_next, int64_t n, void* folded);
+
+/*
  * The two halves of vnm_spmm's matrix-core path as separate calls, for callers that feed the same
  * activations to several layers (the q/k/v projections or the gate/up projections of a block share
  * their input): re-lay X once, multiply many times.  Same arguments and errors as vnm_spmm;

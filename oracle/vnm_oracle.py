@@ -14,6 +14,8 @@ Everything here follows the paper's own wording of the method:
   alternative to |w|; prune() and compress() take any score matrix.
 * Section 4.1 (Eq. 4-5, Appendix B): mask diversity and the two-phase (V, M)
   sifting (mask_diversity_log, select_vm).
+* Section 4.2, Eq. 6: the layer evaluated on a channel-permuted weight
+  (permute_weight, linear_fused_ref, fold_permutations).
 * Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
   input dimension is a multiple of M and the output dimension a multiple of V.
 * Appendix A: the compressed triple -- the compact kept values (A_n), the four
@@ -299,6 +301,46 @@ def max_normalised_error(Y, Y_ref) -> float:
     if denom == 0.0:
         return float(np.max(np.abs(np.asarray(Y, dtype=np.float64)))) if Y_ref.size else 0.0
     return float(np.max(np.abs(np.asarray(Y, dtype=np.float64) - Y_ref)) / denom)
+
+
+# ---------------------------------------------------------------- permuted layer (Section 4.2, Eq. 6)
+
+def permute_weight(W: np.ndarray, perm_out: np.ndarray, perm_in: np.ndarray) -> np.ndarray:
+    """W_p = P_o W P_i of Eq. 6 in index form: row o of W_p is row perm_out[o] of W, column i of
+    W_p is column perm_in[i] of W (P_o[o, perm_out[o]] = 1, P_i[perm_in[i], i] = 1)."""
+    return np.ascontiguousarray(np.asarray(W)[np.asarray(perm_out)][:, np.asarray(perm_in)])
+
+
+def linear_fused_ref(X, Wm_p, bias=None, perm_in=None, perm_out=None) -> np.ndarray:
+    """The layer of Eq. 6 evaluated on the permuted (and pruned) weight, fp64:
+
+      Y = P_o^T W_p P_i^T X  (+ bias),   i.e.   Y[t, perm_out[o]] = bias[o] + sum_i W_p[o, i] X[t, perm_in[i]].
+
+    X fp16 [T x in] in the layer's own channel order, Wm_p [out x in] the masked weight in permuted
+    order, bias [out] in the row order of Wm_p (the bias travels with its row); a missing
+    permutation is the identity.  Returns Y [T x out] in the layer's own channel order.
+    """
+    X = np.asarray(X).astype(np.float64)
+    Xp = X if perm_in is None else X[:, np.asarray(perm_in)]            # P_i^T X
+    Yp = Xp @ np.asarray(Wm_p).astype(np.float64).T                     # W_p (P_i^T X)
+    if bias is not None:
+        Yp = Yp + np.asarray(bias).astype(np.float64)[None, :]
+    if perm_out is None:
+        return Yp
+    Y = np.empty_like(Yp)
+    Y[:, np.asarray(perm_out)] = Yp                                     # P_o^T (...)
+    return Y
+
+
+def fold_permutations(perm_out_prev: np.ndarray, perm_in_next: np.ndarray) -> np.ndarray:
+    """Input permutation of the next layer when the previous layer leaves its output in permuted
+    channel order (its P_o^T is not applied; Section 4.2: the permutations of adjacent layers can
+    be merged).  The previous layer then delivers Z[:, o] = Y[:, perm_out_prev[o]], the next layer
+    needs Y[:, perm_in_next[i]] = Z[:, inverse(perm_out_prev)[perm_in_next[i]]]."""
+    po = np.asarray(perm_out_prev)
+    inv = np.empty_like(po)
+    inv[po] = np.arange(po.size, dtype=po.dtype)
+    return inv[np.asarray(perm_in_next)]
 
 
 # ---------------------------------------------------------------- V and M selection (Section 4.1)

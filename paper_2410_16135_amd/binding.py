@@ -44,6 +44,13 @@ def load_library():
     lib.vnm_prune_compress.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.vnm_pack.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp]
     lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
+    lib.vnm_spmm_fused.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, i64, ci, ci,
+                                   vp, i64, vp]
+    lib.vnm_spmm_fused.restype = ci
+    lib.vnm_spmm_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(i64)]
+    lib.vnm_spmm_fused_workspace_bytes.restype = ci
+    lib.vnm_fold_permutations.argtypes = [vp, vp, i64, vp]
+    lib.vnm_fold_permutations.restype = ci
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
     lib.vnm_stage_x.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     lib.vnm_spmm_staged.argtypes = [vp, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, i64, vp]
@@ -225,6 +232,48 @@ def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO
         _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
         _ptr(ws), ws_bytes, _stream(X)), "vnm_spmm")
     return Y
+
+
+def vnm_spmm_fused(X, c: Compressed, bias=None, perm_in=None, perm_out=None, N: int = 2, out_dtype=None,
+                   path: int = PATH_AUTO, Y=None, workspace=None):
+    """vnm_spmm with an optional bias (fp16 [out], row order of the compressed weight) and the two
+    channel permutations of Eq. 6 (int32 CUDA tensors): Y[t, perm_out[o]] = bias[o] + sum_i W'[o, i]
+    X[t, perm_in[i]].  If perm_out is not a permutation, untouched columns of a fresh Y are undefined."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    T = X.shape[0]
+    assert X.shape[1] == c.inn
+    for name, p, n, dt in (("bias", bias, c.out, torch.float16), ("perm_in", perm_in, c.inn, torch.int32),
+                           ("perm_out", perm_out, c.out, torch.int32)):
+        assert p is None or (p.is_cuda and p.dtype == dt and p.is_contiguous() and p.numel() == n), name
+    if Y is None:
+        Y = torch.empty((T, c.out), dtype=out_dtype or torch.float16, device=X.device)
+    y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    ws, ws_bytes = None, 0
+    if path != PATH_GENERIC and c.packed is not None and T > 0:
+        b = ctypes.c_int64(0)
+        _check(load_library().vnm_spmm_fused_workspace_bytes(T, c.out, c.inn, c.V, N, c.M, int(perm_in is not None),
+                                                             ctypes.byref(b)), "vnm_spmm_fused_workspace_bytes")
+        ws = workspace if workspace is not None else _workspace(X.device, b.value)
+        ws_bytes = ws.numel()
+    _check(load_library().vnm_spmm_fused(
+        _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
+        _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(bias), _ptr(perm_in), _ptr(perm_out), _ptr(Y),
+        Y.stride(0) if T > 0 else c.out, y_dtype, path, _ptr(ws), ws_bytes, _stream(X)), "vnm_spmm_fused")
+    return Y
+
+
+def vnm_fold_permutations(perm_out_prev, perm_in_next):
+    """Host: input permutation of the next layer when the previous one leaves its output in the
+    row order of its (permuted) weight; int32 numpy arrays in, int32 numpy array out."""
+    import numpy as np
+    po = np.ascontiguousarray(perm_out_prev, dtype=np.int32)
+    pi = np.ascontiguousarray(perm_in_next, dtype=np.int32)
+    assert po.ndim == 1 and po.shape == pi.shape
+    res = np.empty_like(po)
+    _check(load_library().vnm_fold_permutations(po.ctypes.data, pi.ctypes.data, po.size, res.ctypes.data),
+           "vnm_fold_permutations")
+    return res
 
 
 def vnm_stage_x(X, M: int, staged=None):

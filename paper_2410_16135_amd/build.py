@@ -4,14 +4,17 @@ from __future__ import annotations
 
 import glob
 import os
+import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libvnm.so")
 
 HIPCC_FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-shared", "-fPIC", "-std=c++17", "-Wno-unused-value",
+    "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wno-unused-value",
     # packed-fp32 VALU forms are kept off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
@@ -22,14 +25,31 @@ def sources():
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into libvnm.so; always recompiles."""
+    """Compile every HIP source (one hipcc process per file, in parallel) and link libvnm.so;
+    always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), *sources(), "-o", LIB_PATH]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    tmp = tempfile.mkdtemp(prefix="vnm_build_")
+    try:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            if res.returncode != 0:
+                raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+            return obj
+        srcs = sources()
+        with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+            objs = list(pool.map(compile_one, srcs))
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc (link) failed:\n" + res.stdout + res.stderr)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB_PATH
 
 

@@ -4,6 +4,7 @@
 #include <mutex>
 #include <set>
 #include <utility>
+#include <vector>
 #include "vnm_internal.h"
 
 namespace vnm {
@@ -122,10 +123,10 @@ extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx
   return launch_pack(values, meta, colidx, make_dims(out, in, V, M), packed, (hipStream_t)stream);
 }
 
-extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
-                        const void* colidx, const void* packed, int64_t out, int64_t in, int V,
-                        int N, int M, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
-                        int64_t workspace_bytes, void* stream) {
+static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                     const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
+                     const Fused& f, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
+                     int64_t workspace_bytes, void* stream) {
   if (!values || !meta || !colidx) return VNM_ERR_NULL;
   if (T != 0 && (!X || !Y)) return VNM_ERR_NULL;                 // an empty batch may come with null X, Y
   int rc = check_pattern(out, in, V, N, M);
@@ -138,31 +139,102 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
   if (((uintptr_t)X & 1) || ((uintptr_t)values & 3)) return VNM_ERR_ALIGN;
   if ((uintptr_t)Y & (y_dtype == 0 ? 1 : 3)) return VNM_ERR_ALIGN;
   if (packed && ((uintptr_t)packed & 255)) return VNM_ERR_ALIGN;
+  if (((uintptr_t)f.bias & 1) || ((uintptr_t)f.perm_in & 15) || ((uintptr_t)f.perm_out & 3)) return VNM_ERR_ALIGN;
   if (T == 0) return VNM_OK;
   Dims d = make_dims(out, in, V, M);
   hipStream_t st = (hipStream_t)stream;
   const bool fast_ok = packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d);
   if (path == VNM_PATH_SMFMAC && !fast_ok) return VNM_ERR_UNSUPPORTED;
-  if (path != VNM_PATH_GENERIC && fast_ok && T <= skinny_max_tokens()) {
+  const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
+  const bool xrow_fits = in * 2 <= permute_rows_max_bytes();          // a row of X fits the permuting pass
+  if (path != VNM_PATH_GENERIC && fast_ok && T <= skinny_max_tokens() && (!f.perm_in || xrow_fits)) {
     // no staging; a workspace, if given, serves as split-K scratch (same offset as for larger T)
-    const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
     const bool have = workspace && ((uintptr_t)workspace & 255) == 0 && workspace_bytes > sb;
-    return launch_spmm_skinny(X, T, ldx, packed, d, Y, ldy, y_dtype, have ? (char*)workspace + sb : nullptr,
-                              have ? workspace_bytes - sb : 0, st);
+    const void* Xk = X;
+    int64_t ldk = ldx;
+    if (f.perm_in) {
+      // the kernel reads a permuted copy of X made at the start of the workspace (the region the
+      // staged activations occupy for larger T, always large enough for 32 rows of X)
+      if (!workspace || workspace_bytes < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;
+      if ((uintptr_t)workspace & 255) return VNM_ERR_ALIGN;
+      rc = launch_permute_rows(X, ldx, workspace, in, T, in, 2, false, f.perm_in, st);   // in % 8 == 0 here
+      if (rc) return rc;
+      Xk = workspace; ldk = in;
+    }
+    return launch_spmm_skinny(Xk, T, ldk, packed, d, Y, ldy, y_dtype, have ? (char*)workspace + sb : nullptr,
+                              have ? workspace_bytes - sb : 0, f, st);
   }
   if (path != VNM_PATH_GENERIC && fast_ok) {
     // the matrix-core kernel streams a re-laid copy of X that lives in the caller's workspace
     if (!workspace || workspace_bytes < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 255) return VNM_ERR_ALIGN;
-    rc = launch_stage_x(X, T, ldx, d, workspace, st);
+    // whatever follows the staged activations serves as split-K scratch, except that with an input
+    // permutation and enough room the tail holds a permuted copy of X (made row by row through
+    // LDS, which keeps every global access contiguous); without the room, or for rows too long for
+    // LDS, the staging pass gathers the permuted columns itself with 2-byte loads (slower).
+    int64_t scratch_bytes = workspace_bytes > sb ? workspace_bytes - sb : 0;
+    const void* Xk = X;
+    int64_t ldk = ldx;
+    const int* stage_perm = f.perm_in;
+    if (f.perm_in && xrow_fits) {
+      const int64_t xp_off = sb + splitk_scratch_bytes(T, out);
+      if (workspace_bytes >= xp_off + T * in * 2) {
+        rc = launch_permute_rows(X, ldx, (char*)workspace + xp_off, in, T, in, 2, false, f.perm_in, st);
+        if (rc) return rc;
+        Xk = (char*)workspace + xp_off; ldk = in; stage_perm = nullptr;
+        scratch_bytes = xp_off - sb;
+      }
+    }
+    rc = launch_stage_x(Xk, T, ldk, d, stage_perm, workspace, st);
     if (rc) return rc;
-    // whatever follows the staged activations serves as split-K scratch
-    const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
-    void* scratch = workspace_bytes > sb ? (char*)workspace + sb : nullptr;
-    return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, scratch,
-                              scratch ? workspace_bytes - sb : 0, st);
+    void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
+    return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
   }
-  return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, st);
+  return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, f, st);
+}
+
+extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                        const void* colidx, const void* packed, int64_t out, int64_t in, int V,
+                        int N, int M, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
+                        int64_t workspace_bytes, void* stream) {
+  return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path,
+                   workspace, workspace_bytes, stream);
+}
+
+extern "C" int vnm_spmm_fused(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                              const void* colidx, const void* packed, int64_t out, int64_t in, int V,
+                              int N, int M, const void* bias, const void* perm_in, const void* perm_out,
+                              void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
+                              int64_t workspace_bytes, void* stream) {
+  Fused f;
+  f.bias = (const _Float16*)bias; f.perm_in = (const int*)perm_in; f.perm_out = (const int*)perm_out;
+  if (in > 0x7FFFFFFF || out > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;   // 32-bit permutation entries
+  return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, f, Y, ldy, y_dtype, path,
+                   workspace, workspace_bytes, stream);
+}
+
+extern "C" int vnm_fold_permutations(const void* perm_out_prev, const void* perm_in_next, int64_t n,
+                                     void* folded) {
+  if (!perm_out_prev || !perm_in_next || !folded) return VNM_ERR_NULL;
+  if (n <= 0 || n > 0x7FFFFFFF) return VNM_ERR_SHAPE;
+  const int* po = (const int*)perm_out_prev;
+  const int* pi = (const int*)perm_in_next;
+  int* res = (int*)folded;
+  // both inputs must be permutations of 0..n-1
+  try {
+  std::vector<int> inv((size_t)n, -1);
+  for (int64_t o = 0; o < n; ++o) {
+    if (po[o] < 0 || po[o] >= n || inv[(size_t)po[o]] >= 0) return VNM_ERR_SHAPE;
+    inv[(size_t)po[o]] = (int)o;
+  }
+  std::vector<char> seen((size_t)n, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    if (pi[i] < 0 || pi[i] >= n || seen[(size_t)pi[i]]) return VNM_ERR_SHAPE;
+    seen[(size_t)pi[i]] = 1;
+  }
+  for (int64_t i = 0; i < n; ++i) res[i] = inv[(size_t)pi[i]];
+  } catch (...) { return VNM_ERR_WORKSPACE; }                              // out of host memory
+  return VNM_OK;
 }
 
 extern "C" int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, int M, void* staged,
@@ -175,7 +247,7 @@ extern "C" int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, in
   if (!spmm_smfmac_applicable(X, ldx, d)) return VNM_ERR_UNSUPPORTED;
   if (staged_bytes_given < staged_bytes(T, d)) return VNM_ERR_WORKSPACE;
   if ((uintptr_t)staged & 255) return VNM_ERR_ALIGN;
-  return launch_stage_x(X, T, ldx, d, staged, (hipStream_t)stream);
+  return launch_stage_x(X, T, ldx, d, nullptr, staged, (hipStream_t)stream);
 }
 
 extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed, int64_t out,
@@ -193,7 +265,7 @@ extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed
   if (scratch && ((uintptr_t)scratch & 255)) return VNM_ERR_ALIGN;
   if (T == 0) return VNM_OK;
   return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype, scratch,
-                            scratch ? scratch_bytes : 0, (hipStream_t)stream);
+                            scratch ? scratch_bytes : 0, Fused{}, (hipStream_t)stream);
 }
 
 extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
@@ -203,6 +275,14 @@ extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int 
   if (rc) return rc;
   if (T < 0) return VNM_ERR_SHAPE;
   *bytes = has_packed(V, M) ? (staged_bytes(T, make_dims(out, in, V, M)) + 255) / 256 * 256 + splitk_scratch_bytes(T, out) : 0;
+  return VNM_OK;
+}
+
+extern "C" int vnm_spmm_fused_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,
+                                             int with_perm_in, int64_t* bytes) {
+  int rc = vnm_spmm_workspace_bytes(T, out, in, V, N, M, bytes);
+  if (rc) return rc;
+  if (with_perm_in && *bytes > 0 && in * 2 <= permute_rows_max_bytes()) *bytes += (T * in * 2 + 255) / 256 * 256;
   return VNM_OK;
 }
 

@@ -134,7 +134,8 @@ __global__ void __launch_bounds__(256)
 spmm_generic_kernel(const _Float16* __restrict__ X, int64_t T, int64_t ldx,
                     const _Float16* __restrict__ values, const unsigned char* __restrict__ meta,
                     const unsigned char* __restrict__ colidx, int64_t out, int64_t in, int V, int M,
-                    int64_t B, OutT* __restrict__ Y, int64_t ldy) {
+                    int64_t B, OutT* __restrict__ Y, int64_t ldy, const _Float16* __restrict__ bias,
+                    const int* __restrict__ perm_in, const int* __restrict__ perm_out) {
   const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t t = blockIdx.y;
   if (o >= out) return;
@@ -149,17 +150,22 @@ spmm_generic_kernel(const _Float16* __restrict__ X, int64_t T, int64_t ldx,
     const unsigned nib = (b & 1) ? (byte >> 4) : (byte & 15u);
     const int64_t c0 = b * M + crow[b * 4 + (nib & 3)];
     const int64_t c1 = b * M + crow[b * 4 + (nib >> 2)];
-    const float x0 = (c0 < in) ? (float)xrow[c0] : 0.f;
-    const float x1 = (c1 < in) ? (float)xrow[c1] : 0.f;
+    // Eq. 6, P_i^T: column c of the weight multiplies input channel perm_in[c]
+    const int64_t s0 = (c0 < in) ? (perm_in ? (int64_t)perm_in[c0] : c0) : -1;
+    const int64_t s1 = (c1 < in) ? (perm_in ? (int64_t)perm_in[c1] : c1) : -1;
+    const float x0 = (s0 >= 0 && s0 < in) ? (float)xrow[s0] : 0.f;
+    const float x1 = (s1 >= 0 && s1 < in) ? (float)xrow[s1] : 0.f;
     acc = fmaf((float)vrow[2 * b], x0, acc);
     acc = fmaf((float)vrow[2 * b + 1], x1, acc);
   }
-  Y[t * ldy + o] = (OutT)acc;
+  if (bias) acc += (float)bias[o];
+  const int64_t dst = perm_out ? (int64_t)perm_out[o] : o;                  // Eq. 6, P_o^T
+  if (dst >= 0 && dst < out) Y[t * ldy + dst] = (OutT)acc;
 }
 
 int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                         const void* colidx, const Dims& d, void* Y, int64_t ldy, int y_dtype,
-                        hipStream_t st) {
+                        const Fused& f, hipStream_t st) {
   const unsigned gx = (unsigned)((d.out + 255) / 256);
   for (int64_t t0 = 0; t0 < T; t0 += 65535) {                    // grid.y limit
     const int64_t nt = T - t0 < 65535 ? T - t0 : 65535;
@@ -168,12 +174,12 @@ int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* value
       hipLaunchKernelGGL(spmm_generic_kernel<_Float16>, dim3(gx, (unsigned)nt), dim3(256), 0, st, Xs,
                          nt, ldx, (const _Float16*)values, (const unsigned char*)meta,
                          (const unsigned char*)colidx, d.out, d.in, d.V, d.M, d.B,
-                         (_Float16*)Y + t0 * ldy, ldy);
+                         (_Float16*)Y + t0 * ldy, ldy, f.bias, f.perm_in, f.perm_out);
     else
       hipLaunchKernelGGL(spmm_generic_kernel<float>, dim3(gx, (unsigned)nt), dim3(256), 0, st, Xs,
                          nt, ldx, (const _Float16*)values, (const unsigned char*)meta,
                          (const unsigned char*)colidx, d.out, d.in, d.V, d.M, d.B,
-                         (float*)Y + t0 * ldy, ldy);
+                         (float*)Y + t0 * ldy, ldy, f.bias, f.perm_in, f.perm_out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e, "spmm_generic_kernel"); return VNM_ERR_HIP; }
   }

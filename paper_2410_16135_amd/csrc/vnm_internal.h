@@ -63,6 +63,16 @@ constexpr int kImagePitch = kTokTile * 2 + 64;
 inline int64_t image_bytes(int M) { return ((int64_t)8 * M * kImagePitch + 1023) / 1024 * 1024; }
 int64_t staged_bytes(int64_t T, const Dims& d);
 
+// Optional steps fused around the product (Section 4.2, Eq. 6, plus the layer's bias); all null = the
+// plain product.  Entries of a permutation outside its range never fault: such an input column reads
+// as zero, such an output channel is not stored.
+struct Fused {
+  const _Float16* bias = nullptr;   // [out], in the row order of the compressed weight
+  const int* perm_in = nullptr;     // [in]:  column i of the weight multiplies X[:, perm_in[i]]
+  const int* perm_out = nullptr;    // [out]: row o of the weight produces Y[:, perm_out[o]]
+  bool any_out() const { return bias || perm_out; }
+};
+
 void set_hip_error(hipError_t e, const char* where);
 // Raises a kernel's dynamic-LDS limit to the 160 KiB of a gfx950 CU, once per (kernel, device); thread-safe.
 // Returns a vnm_status.
@@ -83,8 +93,16 @@ int launch_decompress(const void* values, const void* meta, const void* colidx, 
                       void* W_out, int64_t ldw, hipStream_t st);
 int launch_spmm_generic(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                         const void* colidx, const Dims& d, void* Y, int64_t ldy, int y_dtype,
-                        hipStream_t st);
-int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st);
+                        const Fused& f, hipStream_t st);
+// perm_in (or null): image row c of K step s holds X[:, perm_in[8 M s + c]]
+int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, const int* perm_in, void* Xs,
+                   hipStream_t st);
+// Row-wise channel permutation through LDS: gather (dst[t, j] = src[t, idx[j]]) or scatter
+// (dst[t, idx[j]] = src[t, j], in place allowed); rows of n elements of 2 or 4 bytes, at most
+// permute_rows_max_bytes() per row.
+int64_t permute_rows_max_bytes();
+int launch_permute_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int64_t n,
+                        int elem_bytes, bool scatter, const int* idx, hipStream_t st);
 bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d);
 // Importance scores other than |w| (vnm_score.hip)
 int launch_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act, void* S,
@@ -95,14 +113,15 @@ int launch_prune_scored(const void* W, int64_t ldw, const void* S, int64_t lds, 
 int64_t skinny_max_tokens();
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
-                       hipStream_t st);
-// Y = sum of KS fp32 partial products [KS][T][out] held in `part`
+                       const Fused& f, hipStream_t st);
+// Y = sum of KS fp32 partial products [KS][T][out] held in `part` (+ bias, output permutation)
 int launch_splitk_reduce(const void* part, int KS, int64_t T, int64_t out, void* Y, int64_t ldy,
-                         int y_dtype, hipStream_t st);
+                         int y_dtype, const Fused& f, hipStream_t st);
 // Split-K scratch of the product kernel for small token counts (fp32 partial products), 0 when unused.
 int64_t splitk_scratch_bytes(int64_t T, int64_t out);
+// f.perm_in is not this kernel's business (it is applied when X is staged)
 int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
-                       hipStream_t st);
+                       const Fused& f, hipStream_t st);
 
 }  // namespace vnm

@@ -35,6 +35,8 @@ struct SkinnyArgs {
   // split K: workgroup (r, z) walks phases [z * npz, min(nph, (z + 1) * npz)) and writes its fp32
   // partial product at Y + z * z_stride elements (a scratch then; summed by splitk_reduce)
   int npz; int64_t z_stride;
+  // fused epilogue (null = none): bias per weight row, destination channel per weight row
+  const _Float16* bias; const int* perm_out;
 };
 
 // DUAL: the 64-row block carries one column table per 32-row tile (V = 32 patterns) instead of one
@@ -189,8 +191,11 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < kSkWaves; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
-      if (a.y_fp32) ((float*)a.Y)[(int64_t)blockIdx.y * a.z_stride + tok * a.ldy + o] = sum;
-      else ((_Float16*)a.Y)[tok * a.ldy + o] = (_Float16)sum;
+      if (a.bias) sum += (float)a.bias[o];
+      const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
+      if (dst < 0 || dst >= a.out) continue;
+      if (a.y_fp32) ((float*)a.Y)[(int64_t)blockIdx.y * a.z_stride + tok * a.ldy + dst] = sum;
+      else ((_Float16*)a.Y)[tok * a.ldy + dst] = (_Float16)sum;
     }
   }
 }
@@ -213,19 +218,20 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
 
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
-                       hipStream_t st) {
+                       const Fused& f, hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
   const bool dual = packed_tables(d.V) == 2;
   const int64_t R = packed_row_blocks(d);
   if (R > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
-  SkinnyArgs a;
+  SkinnyArgs a{};
   a.X = (const unsigned short*)X; a.T = T; a.ldx = ldx; a.in = d.in;
   a.pa = (const uint4*)(p + pl.pa_off);
   a.pidx = (const unsigned short*)(p + pl.pidx_off);
   a.pcol = (const uint4*)(p + pl.pcol_off);
   a.out = d.out; a.S = d.S; a.M = d.M;
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
+  a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
   // steps per phase: a multiple of the 8 waves, at most 32, with at most kSkNX pieces of X per thread
   // (TT * P * M <= 512 * kSkNX), which also keeps the two LDS buffers below 132 KiB
@@ -249,12 +255,15 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
       KS = (nph + a.npz - 1) / a.npz;
     }
   }
-  if (KS > 1) { a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out; }
+  if (KS > 1) {
+    a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
+    a.bias = nullptr; a.perm_out = nullptr;                               // applied by the reduction
+  }
   int rc = VNM_ERR_UNSUPPORTED;
   if (!dual) rc = TT == 16 ? launch_skinny_cfg<false, 16>(a, R, KS, st) : launch_skinny_cfg<false, 32>(a, R, KS, st);
   else rc = TT == 16 ? launch_skinny_cfg<true, 16>(a, R, KS, st) : launch_skinny_cfg<true, 32>(a, R, KS, st);
   if (rc != VNM_OK || KS == 1) return rc;
-  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);
+  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, f, st);
 }
 
 }  // namespace vnm

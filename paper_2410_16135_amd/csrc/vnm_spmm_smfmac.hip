@@ -185,7 +185,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
       VNM_ASM_ADDR("233")                                                                         \
       VNM_ASM_READ4(0, 192, 194, 196, 198)                                                        \
       VNM_ASM_READ4(64, 200, 202, 204, 206)                                                       \
-      "1:\n"                                                                                      \
+      "1:\n"                                                                                \
       VNM_ASM_STEP("224:227", "228:231", "232", "243", "244:247", "248:251", "252", "253", COPY_A, COPY_B, VMWSTR) \
       VNM_ASM_STEP("234:237", "238:241", "242", "253", "224:227", "228:231", "232", "233", COPY_A, COPY_B, VMWSTR) \
       VNM_ASM_STEP("244:247", "248:251", "252", "233", "234:237", "238:241", "242", "243", COPY_A, COPY_B, VMWSTR) \
@@ -306,7 +306,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
       VNM_D_READ4(0, 188, 180)                                                                    \
       VNM_D_READ4(0, 196, 184)                                                                    \
       VNM_D_READ4(64, 204, 180)                                                                   \
-      "1:\n"                                                                                      \
+      "1:\n"                                                                                \
       VNM_D_STEP("220:223", "224:227", "230", "240", "241", "244:247", "248:251", "243", "252:253", COPY_A, COPY_B, VMWSTR) \
       VNM_D_STEP("232:235", "236:239", "242", "252", "253", "220:223", "224:227", "230", "228:229", COPY_A, COPY_B, VMWSTR) \
       VNM_D_STEP("244:247", "248:251", "243", "228", "229", "232:235", "236:239", "242", "240:241", COPY_A, COPY_B, VMWSTR) \
@@ -346,13 +346,17 @@ struct SpmmArgs {
   // split K: workgroup z handles K steps [z * ks_steps, min(S, (z + 1) * ks_steps)) and writes its
   // partial product to Y + z * z_stride elements (an fp32 scratch then, summed by a second kernel)
   int64_t ks_steps, z_stride;
+  // fused epilogue (null = none): bias per weight row, destination channel per weight row
+  const _Float16* bias; const int* perm_out;
 };
 
 // One K step = 8 column blocks = 8*M raw input columns = 32 compacted K = one staged image.
 // NCW: wave-wide 1 KiB copies per wave and image (V = 64 assembly loop; 0 elsewhere).
 // NBUF: depth of the LDS image ring.
 // DUAL: the packed row blocks carry two column tables (V = 32 patterns), assembly loop only.
-template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL>
+// FUSED: the epilogue looks at bias and perm_out (the plain instantiation ignores them and is exactly
+// the kernel the benchmark times).
+template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL, bool FUSED>
 __global__ void __launch_bounds__(64 * WR * WT)
 spmm_smfmac_kernel(const SpmmArgs a) {
   constexpr int AT = V / 32, BT = TW / 32, NW = WR * WT;
@@ -454,7 +458,28 @@ spmm_smfmac_kernel(const SpmmArgs a) {
   // V/8 lanes per token, and stored as whole V*2-byte runs of each Y row.
   if (!r_valid) return;
   const int tokl = lane & 31;
-  if (!a.y_fp32 && a.wide_store) {
+  if constexpr (FUSED) {
+    if (a.bias) {
+      // bias of output channel r V + 32 i + 8 jq + 4 hB + e, the channel this lane holds in
+      // accumulator element 4 jq + e of A tile i.  All loads are issued before the first use
+      // (unconditional, index clamped: rows beyond `out` are never stored, whatever is added there).
+      float bv[AT][16];
+#pragma unroll
+      for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          const int64_t o = r * V + i * 32 + 8 * (k >> 2) + 4 * hB + (k & 3);
+          bv[i][k] = (float)a.bias[o < a.out ? o : a.out - 1];
+        }
+#pragma unroll
+      for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+#pragma unroll
+          for (int j = 0; j < BT; ++j) acc[i][j][k] += bv[i][k];
+    }
+  }
+  if (!a.y_fp32 && a.wide_store && (!FUSED || !a.perm_out)) {
     constexpr int EP = V * 2 + 8;                         // bytes per token row in LDS
     unsigned char* ep = smem + (size_t)wave * TW * EP;    // this wave's private region
 #pragma unroll
@@ -509,6 +534,30 @@ spmm_smfmac_kernel(const SpmmArgs a) {
       if (o + 3 < a.out) dst[3] = (OutT)v3;
     }
   };
+  if (FUSED && a.perm_out) {
+    // Output permutation (Eq. 6, P_o^T): channel o of the weight's row order goes to column
+    // perm_out[o] of Y, one 2- or 4-byte store per element (rows of Y are token-major, so a
+    // permutation of the channels leaves nothing contiguous); split-K partials never come here.
+#pragma unroll
+    for (int i = 0; i < AT; ++i)
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t o = r * V + i * 32 + 8 * jq + 4 * hB + e;
+          const int64_t dst = o < a.out ? (int64_t)a.perm_out[o] : -1;
+          if (dst < 0 || dst >= a.out) continue;
+#pragma unroll
+          for (int j = 0; j < BT; ++j) {
+            const int64_t tok = t0 + wt * TW + j * 32 + tokl;
+            if (tok >= a.T) continue;
+            const float v = acc[i][j][4 * jq + e];
+            if (a.y_fp32) ((float*)a.Y)[tok * a.ldy + dst] = v;
+            else ((_Float16*)a.Y)[tok * a.ldy + dst] = (_Float16)v;
+          }
+        }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < BT; ++j) {
     const int64_t tok = t0 + wt * TW + j * 32 + tokl;
@@ -531,12 +580,12 @@ bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d) {
   return has_packed(d.V, d.M) && d.in % 8 == 0 && ldx % 8 == 0 && ((uintptr_t)X & 15) == 0;
 }
 
-template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL>
-static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
+template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL, bool FUSED>
+static int launch_cfg2(const SpmmArgs& a, hipStream_t st) {
   size_t lds = (size_t)NBUF * a.image_bytes;
   const size_t ep = (size_t)WR * WT * TW * (V * 2 + 8);     // epilogue transposition, per wave [TW][V] fp16
   if (ep > lds) lds = ep;
-  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF, DUAL>;
+  auto kern = spmm_smfmac_kernel<V, TW, WR, WT, NCW, NBUF, DUAL, FUSED>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_smfmac)")) return rc_lds;
   dim3 grid((unsigned)((a.T + kTokTile - 1) / kTokTile), (unsigned)((a.R + WR - 1) / WR),
             (unsigned)((a.S + a.ks_steps - 1) / a.ks_steps));
@@ -544,6 +593,12 @@ static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_smfmac_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
+}
+
+template <int V, int TW, int WR, int WT, int NCW, int NBUF, bool DUAL>
+static int launch_cfg(const SpmmArgs& a, hipStream_t st) {
+  if (a.bias || a.perm_out) return launch_cfg2<V, TW, WR, WT, NCW, NBUF, DUAL, true>(a, st);
+  return launch_cfg2<V, TW, WR, WT, NCW, NBUF, DUAL, false>(a, st);
 }
 
 // V = 64: pick the assembly loop by workgroup size (4 or 8 row blocks), by copies per wave
@@ -575,10 +630,12 @@ static int launch_v64_w8(const SpmmArgs& a, hipStream_t st) {
   return VNM_ERR_UNSUPPORTED;
 }
 
-// Sum of the KS fp32 partial products [KS][T][out] into Y (fp16 or fp32, leading dimension ldy).
+// Sum of the KS fp32 partial products [KS][T][out] into Y (fp16 or fp32, leading dimension ldy),
+// plus the fused bias and output permutation if given.
 template <typename OutT>
 __global__ void __launch_bounds__(256)
-splitk_reduce_kernel(const float* __restrict__ part, int KS, int64_t T, int64_t out, OutT* __restrict__ Y, int64_t ldy) {
+splitk_reduce_kernel(const float* __restrict__ part, int KS, int64_t T, int64_t out, OutT* __restrict__ Y, int64_t ldy,
+                     const _Float16* __restrict__ bias, const int* __restrict__ perm_out) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= T * out) return;
   float acc = 0.f;
@@ -592,7 +649,9 @@ splitk_reduce_kernel(const float* __restrict__ part, int KS, int64_t T, int64_t 
   }
   for (; z < KS; ++z) acc += p[(int64_t)z * zs];
   const int64_t t = idx / out, o = idx - t * out;
-  Y[t * ldy + o] = (OutT)acc;
+  if (bias) acc += (float)bias[o];
+  const int64_t dst = perm_out ? (int64_t)perm_out[o] : o;
+  if (dst >= 0 && dst < out) Y[t * ldy + dst] = (OutT)acc;
 }
 
 constexpr int64_t kSplitKMaxTokens = 256;
@@ -607,10 +666,11 @@ int64_t splitk_scratch_bytes(int64_t T, int64_t out) {
 
 int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
-                       hipStream_t st) {
+                       const Fused& f, hipStream_t st) {
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
-  SpmmArgs a;
+  SpmmArgs a{};
+  a.bias = f.bias; a.perm_out = f.perm_out;
   a.Xs = (const unsigned char*)Xs; a.T = T;
   a.pa = (const uint4*)(p + pl.pa_off);
   a.pidx = (const unsigned short*)(p + pl.pidx_off);
@@ -647,8 +707,15 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
   }
   if (KS > 1) {
     a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
+    a.bias = nullptr; a.perm_out = nullptr;                           // applied by the reduction
     wide = false;
   }
+  // Output permutation: rather than scattering 2-byte stores from the epilogue, Y is written in the
+  // weight's row order (contiguous runs) and its rows are permuted in place by a second pass
+  // through LDS while they are still in cache; rows too long for LDS take the scattering epilogue.
+  const int y_elem = y_dtype == 0 ? 2 : 4;
+  const bool post_permute = KS == 1 && f.perm_out && d.out * y_elem <= permute_rows_max_bytes();
+  if (post_permute) a.perm_out = nullptr;
   a.wide_store = (a.y_fp32 == 0) && (a.ldy % 8 == 0) && (((uintptr_t)a.Y & 15) == 0);
   a.vec_store = (a.ldy % 4 == 0) && (((uintptr_t)a.Y & (a.y_fp32 == 0 ? 7 : 15)) == 0);
   int rc = VNM_ERR_UNSUPPORTED;
@@ -660,19 +727,21 @@ int launch_spmm_smfmac(const void* Xs, int64_t T, const void* packed, const Dims
     if (wide) rc = ring4 ? launch_v64_w8<4, true>(a, st) : launch_v64_w8<3, true>(a, st);
     else rc = deep ? launch_v64_w4<4, true>(a, st) : launch_v64_w4<3, true>(a, st);
   }
-  if (rc != VNM_OK || KS == 1) return rc;
-  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, st);
+  if (rc != VNM_OK) return rc;
+  if (post_permute) return launch_permute_rows(Y, ldy, Y, ldy, T, d.out, y_elem, true, f.perm_out, st);
+  if (KS == 1) return rc;
+  return launch_splitk_reduce(scratch, KS, T, d.out, Y, ldy, y_dtype, f, st);
 }
 
 int launch_splitk_reduce(const void* part, int KS, int64_t T, int64_t out, void* Y, int64_t ldy,
-                         int y_dtype, hipStream_t st) {
+                         int y_dtype, const Fused& f, hipStream_t st) {
   const int64_t n = T * out;
   if (y_dtype == 0)
     hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       (const float*)part, KS, T, out, (_Float16*)Y, ldy);
+                       (const float*)part, KS, T, out, (_Float16*)Y, ldy, f.bias, f.perm_out);
   else
     hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       (const float*)part, KS, T, out, (float*)Y, ldy);
+                       (const float*)part, KS, T, out, (float*)Y, ldy, f.bias, f.perm_out);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "splitk_reduce_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

@@ -19,10 +19,16 @@ namespace vnm {
 // [token][column]; the tile is read back column-wise and written 16 bytes (8 tokens of one column)
 // per lane, 16 lanes per image row.  The loads of the next sub-chunk are issued before the stores
 // of the current one, so that reads and writes of HBM overlap inside every workgroup.
-template <int kStageKC>
+//
+// GATHER: an input-channel permutation (Section 4.2, Eq. 6: the factor P_i^T applied to X) is folded
+// into this pass, which copies every element anyway: image row c of K step s takes column
+// perm[8 M s + c] of X, fetched with 2-byte loads (a permutation of the channels leaves nothing
+// contiguous in a token's row).
+template <int kStageKC, bool GATHER>
 __global__ void __launch_bounds__(256)
 stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int64_t in, int M,
-               int64_t S, int64_t image_bytes, int n_sub, unsigned char* __restrict__ Xs) {
+               int64_t S, int64_t image_bytes, int n_sub, const int* __restrict__ perm,
+               unsigned char* __restrict__ Xs) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int64_t tile = blockIdx.x;
   const int64_t sub0 = (int64_t)blockIdx.y * n_sub;
@@ -42,7 +48,17 @@ stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int
     for (int i = 0; i < 16; ++i) {
       if (i < NI) {
         w[i] = make_uint4(0, 0, 0, 0);
-        if (t0 + tok < T && col0 + ch * 8 < in) w[i] = *(const uint4*)(X + (t0 + tok) * ldx + col0 + ch * 8);
+        if (!GATHER) {
+          if (t0 + tok < T && col0 + ch * 8 < in) w[i] = *(const uint4*)(X + (t0 + tok) * ldx + col0 + ch * 8);
+        } else if (t0 + tok < T && col0 + ch * 8 < in) {               // in % 8 == 0: all 8 entries exist
+          const int4 p0 = *(const int4*)(perm + col0 + ch * 8), p1 = *(const int4*)(perm + col0 + ch * 8 + 4);
+          const int pc[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+          const unsigned short* xr = X + (t0 + tok) * ldx;
+          unsigned h[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) h[e] = (unsigned)pc[e] < (unsigned)in ? xr[pc[e]] : 0u;   // (in < 2^31)
+          w[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        }
         ch += dch; tok += dtok;
         if (ch >= CH) { ch -= CH; ++tok; }
       }
@@ -90,13 +106,141 @@ stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int
   }
 }
 
+// Channel permutation of the rows of a token-major matrix (Section 4.2, Eq. 6), one workgroup per
+// token row, the whole row passing through LDS so that both the global reads and the global writes
+// are contiguous and only the LDS accesses are scattered:
+//   SCATTER = false:  dst[t, j] = src[t, idx[j]]      (P_i^T applied to X; an entry of idx outside
+//                                                      0..n-1 gives 0)
+//   SCATTER = true:   dst[t, idx[j]] = src[t, j]      (P_o^T applied to Y; an entry outside the range
+//                                                      is dropped, columns nothing maps to become 0)
+// dst may be src (each workgroup reads its whole row before it writes any of it).
+// VEC: 16-byte global accesses (n a multiple of 16 / sizeof(E), rows 16-byte aligned).
+// The gather form may split a row's destination over gridDim.y workgroups (each reads the whole
+// source row, which then comes from L2): few rows alone would leave most of the chip idle.
+template <typename E, bool SCATTER, bool VEC>
+__global__ void __launch_bounds__(256)
+permute_rows_kernel(const E* __restrict__ src, int64_t ld_src, E* dst, int64_t ld_dst, int64_t n,
+                    const int* __restrict__ idx) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  E* row = (E*)smem;
+  constexpr int EPV = 16 / (int)sizeof(E);             // elements per 16-byte vector
+  const int64_t t = blockIdx.x;
+  const E* s = src + t * ld_src;
+  E* d = dst + t * ld_dst;
+  const int tid = threadIdx.x;
+  if (SCATTER) {
+    if (VEC) {
+      const int64_t nv = n / EPV;
+      for (int64_t v = tid; v < nv; v += 256) ((uint4*)row)[v] = make_uint4(0, 0, 0, 0);
+      __syncthreads();
+      for (int64_t v = tid; v < nv; v += 256) {
+        const uint4 w = ((const uint4*)s)[v];
+        const E* e = (const E*)&w;
+        int k[EPV];
+#pragma unroll
+        for (int q = 0; q < EPV / 4; ++q) *(int4*)(k + 4 * q) = ((const int4*)idx)[v * (EPV / 4) + q];
+#pragma unroll
+        for (int q = 0; q < EPV; ++q)
+          if ((unsigned)k[q] < (unsigned)n) row[k[q]] = e[q];
+      }
+      __syncthreads();
+      for (int64_t v = tid; v < nv; v += 256) ((uint4*)d)[v] = ((const uint4*)row)[v];
+    } else {
+      for (int64_t j = tid; j < n; j += 256) row[j] = (E)0;
+      __syncthreads();
+      for (int64_t j = tid; j < n; j += 256) {
+        const int k = idx[j];
+        const E v = s[j];
+        if ((unsigned)k < (unsigned)n) row[k] = v;
+      }
+      __syncthreads();
+      for (int64_t j = tid; j < n; j += 256) d[j] = row[j];
+    }
+  } else {
+    // destination range of this workgroup
+    const int64_t per = ((n + gridDim.y - 1) / gridDim.y + EPV - 1) / EPV * EPV;
+    const int64_t j0 = (int64_t)blockIdx.y * per, j1 = j0 + per < n ? j0 + per : n;
+    if (VEC) {
+      const int64_t nv = n / EPV;
+      for (int64_t v = tid; v < nv; v += 256) ((uint4*)row)[v] = ((const uint4*)s)[v];
+      __syncthreads();
+      for (int64_t v = j0 / EPV + tid; v < j1 / EPV; v += 256) {
+        int k[EPV];
+#pragma unroll
+        for (int q = 0; q < EPV / 4; ++q) *(int4*)(k + 4 * q) = ((const int4*)idx)[v * (EPV / 4) + q];
+        uint4 w;
+        E* e = (E*)&w;
+#pragma unroll
+        for (int q = 0; q < EPV; ++q) e[q] = (unsigned)k[q] < (unsigned)n ? row[k[q]] : (E)0;
+        ((uint4*)d)[v] = w;
+      }
+    } else {
+      for (int64_t j = tid; j < n; j += 256) row[j] = s[j];
+      __syncthreads();
+      for (int64_t j = j0 + tid; j < j1; j += 256) {
+        const int k = idx[j];
+        d[j] = (unsigned)k < (unsigned)n ? row[k] : (E)0;
+      }
+    }
+  }
+}
+
+int64_t permute_rows_max_bytes() { return 144 * 1024; }
+
+template <typename E, bool SCATTER, bool VEC>
+static int launch_permute_cfg(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int64_t n,
+                              const int* idx, hipStream_t st) {
+  auto kern = permute_rows_kernel<E, SCATTER, VEC>;
+  if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(permute_rows)")) return rc_lds;
+  // gather form: split rows until about two workgroups per CU exist
+  int64_t ny = 1;
+  if (!SCATTER && T < 512) { ny = 512 / T; if (ny > 16) ny = 16; if (ny * 2048 > n) ny = n / 2048 > 0 ? n / 2048 : 1; }
+  hipLaunchKernelGGL(kern, dim3((unsigned)T, (unsigned)ny), dim3(256), (size_t)n * sizeof(E), st, (const E*)src,
+                     ld_src, (E*)dst, ld_dst, n, idx);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "permute_rows_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
+template <typename E>
+static int launch_permute_e(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int64_t n,
+                            bool scatter, const int* idx, hipStream_t st) {
+  const int64_t epv = 16 / (int64_t)sizeof(E);
+  const bool vec = n % epv == 0 && ld_src % epv == 0 && ld_dst % epv == 0 && (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)idx) & 15) == 0;
+  if (scatter)
+    return vec ? launch_permute_cfg<E, true, true>(src, ld_src, dst, ld_dst, T, n, idx, st)
+               : launch_permute_cfg<E, true, false>(src, ld_src, dst, ld_dst, T, n, idx, st);
+  return vec ? launch_permute_cfg<E, false, true>(src, ld_src, dst, ld_dst, T, n, idx, st)
+             : launch_permute_cfg<E, false, false>(src, ld_src, dst, ld_dst, T, n, idx, st);
+}
+
+int launch_permute_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int64_t n,
+                        int elem_bytes, bool scatter, const int* idx, hipStream_t st) {
+  if (T > 0x7FFFFFFF || n * elem_bytes > permute_rows_max_bytes()) return VNM_ERR_UNSUPPORTED;
+  if (elem_bytes == 2) return launch_permute_e<unsigned short>(src, ld_src, dst, ld_dst, T, n, scatter, idx, st);
+  return launch_permute_e<unsigned>(src, ld_src, dst, ld_dst, T, n, scatter, idx, st);
+}
+
 int64_t staged_bytes(int64_t T, const Dims& d) {
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
   // + 3 images that the product kernel's look-ahead copies may read (never use) past the last tile
   return (tiles * d.S + 3) * image_bytes(d.M);
 }
 
-int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* Xs, hipStream_t st) {
+template <int KC, bool GATHER>
+static int launch_stage_cfg(const void* X, int64_t T, int64_t ldx, const Dims& d, const int* perm, void* Xs,
+                            dim3 grid, size_t lds, int n_sub, hipStream_t st) {
+  auto kern = stage_x_kernel<KC, GATHER>;
+  if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(stage_x)")) return rc_lds;
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M, d.S,
+                     image_bytes(d.M), n_sub, perm, (unsigned char*)Xs);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "stage_x_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
+int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, const int* perm_in, void* Xs,
+                   hipStream_t st) {
   const int64_t tiles = (T + kTokTile - 1) / kTokTile;
   // K steps per sub-chunk: 4 (rows of 64 M bytes per load) while a thread's share fits 16 registers sets
   const int KC = d.M <= 8 ? 4 : 2;
@@ -107,18 +251,12 @@ int launch_stage_x(const void* X, int64_t T, int64_t ldx, const Dims& d, void* X
   const int64_t gy = (subs + n_sub - 1) / n_sub;
   if (tiles > 0x7FFFFFFF || gy > 65535) return VNM_ERR_UNSUPPORTED;
   const size_t lds = (size_t)kTokTile * (KC * d.M * 16 + 4);
-  if (int rc_lds = allow_big_lds(KC == 4 ? (const void*)stage_x_kernel<4> : (const void*)stage_x_kernel<2>,
-                                 "hipFuncSetAttribute(stage_x)")) return rc_lds;
   dim3 grid((unsigned)tiles, (unsigned)gy);
   if (KC == 4)
-    hipLaunchKernelGGL(stage_x_kernel<4>, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,
-                       d.S, image_bytes(d.M), (int)n_sub, (unsigned char*)Xs);
-  else
-    hipLaunchKernelGGL(stage_x_kernel<2>, grid, dim3(256), lds, st, (const unsigned short*)X, T, ldx, d.in, d.M,
-                       d.S, image_bytes(d.M), (int)n_sub, (unsigned char*)Xs);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) { set_hip_error(e, "stage_x_kernel"); return VNM_ERR_HIP; }
-  return VNM_OK;
+    return perm_in ? launch_stage_cfg<4, true>(X, T, ldx, d, perm_in, Xs, grid, lds, (int)n_sub, st)
+                   : launch_stage_cfg<4, false>(X, T, ldx, d, nullptr, Xs, grid, lds, (int)n_sub, st);
+  return perm_in ? launch_stage_cfg<2, true>(X, T, ldx, d, perm_in, Xs, grid, lds, (int)n_sub, st)
+                 : launch_stage_cfg<2, false>(X, T, ldx, d, nullptr, Xs, grid, lds, (int)n_sub, st);
 }
 
 }  // namespace vnm

@@ -236,6 +236,15 @@ int vnm_mask_diversity_log(int V, int N, int M, double* ln_k);
 int vnm_select_vm(const int* V, const int* M, const double* speedup, int n, double threshold,
                   int* selected);
 
+/*
+ * Host only.  Linear sum assignment (Section 4.2: every half-step of the permutation search is
+ * modelled as one and solved by the Hungarian algorithm): assign[i] = the column given to row i such
+ * that sum_i gain[i, assign[i]] is maximal; *total = that sum.  gain: int64 [n x n], row-major,
+ * entries in [0, 2^60]; assign: int32 [n].  Exact integer arithmetic, O(n^3).  Among equally good
+ * assignments which one is returned is unspecified.
+ */
+int vnm_lsa_max(const void* gain, int n, void* assign, int64_t* total);
+
 const char* vnm_status_string(int status);
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char* vnm_last_hip_error(void);

@@ -15,7 +15,8 @@ Everything here follows the paper's own wording of the method:
 * Section 4.1 (Eq. 4-5, Appendix B): mask diversity and the two-phase (V, M)
   sifting (mask_diversity_log, select_vm).
 * Section 4.2, Eq. 6: the layer evaluated on a channel-permuted weight
-  (permute_weight, linear_fused_ref, fold_permutations).
+  (permute_weight, linear_fused_ref, fold_permutations); Eqs. 7-9: the search
+  for the permutations (permutation_search and its parts).
 * Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
   input dimension is a multiple of M and the output dimension a multiple of V.
 * Appendix A: the compressed triple -- the compact kept values (A_n), the four
@@ -341,6 +342,102 @@ def fold_permutations(perm_out_prev: np.ndarray, perm_in_next: np.ndarray) -> np
     inv = np.empty_like(po)
     inv[po] = np.arange(po.size, dtype=po.dtype)
     return inv[np.asarray(perm_in_next)]
+
+
+# ---------------------------------------------------------------- permutation search (Section 4.2, Eqs. 7-9)
+#
+# The paper states the objective (Eq. 7: the retained importance after V:N:M pruning of the permuted
+# matrix), the alternation (Eqs. 8-9, two iterations, both permutations start as the identity) and
+# that each half-step is "approximately modelled" as a linear sum assignment problem solved by the
+# Hungarian algorithm; it does not print the modelling.  The reading taken here: a half-step visits
+# the in-block positions ("slots") one after the other; for slot q the channel at position q of
+# every full block is lifted out, gain[b, k] is the retained importance of block k if the channel
+# lifted from block b is put into its free position, and the assignment of lifted channels to
+# blocks that maximises the total gain is applied.  The identity assignment reproduces the current
+# state, so no step lowers the objective.  Importance scores are quantised once to non-negative
+# integers (rint(score * scale), at most 2**32 - 1): all sums are then exact, whatever their order.
+# Channels of a ragged last block stay where they are.
+
+def quantise_scores(S: np.ndarray, scale: float) -> np.ndarray:
+    """Integer scores used by the search: rint(S * scale) in fp64, clipped to [0, 2**32 - 1]; int64."""
+    q = np.rint(np.asarray(S, dtype=np.float64) * float(scale))
+    return np.clip(q, 0, 2.0 ** 32 - 1).astype(np.int64)
+
+
+def retained_score(Sq: np.ndarray, V: int, M: int) -> int:
+    """Objective of Eq. 7 for the matrix as it stands: sum of the scores that V:N:M pruning keeps
+    when the scores themselves drive it (Section 3 steps 2-3, ties to the lower index)."""
+    Sq = np.asarray(Sq, dtype=np.int64)
+    _, _, mask = prune(np.zeros(Sq.shape, dtype=np.float16), V, M, score=Sq.astype(np.float64))
+    return int(Sq[mask == 1].sum())
+
+
+def permutation_objective(Sq, V: int, M: int, perm_out, perm_in) -> int:
+    """Eq. 7 for given permutations: retained score of Sq[perm_out][:, perm_in]."""
+    return retained_score(np.asarray(Sq)[np.asarray(perm_out)][:, np.asarray(perm_in)], V, M)
+
+
+def perm_gain_in(Sp: np.ndarray, V: int, M: int, slot: int) -> np.ndarray:
+    """Input half-step (Eq. 8), one slot: gain[b, k] = retained score of column block k (all rows)
+    with its column at position `slot` replaced by the column at that position of block b.
+    Sp is the matrix in its current permuted order; full blocks only.  int64 [B, B]."""
+    Bf = Sp.shape[1] // M
+    gain = np.zeros((Bf, Bf), dtype=np.int64)
+    for k in range(Bf):
+        for b in range(Bf):
+            blk = Sp[:, k * M:(k + 1) * M].copy()
+            blk[:, slot] = Sp[:, b * M + slot]
+            gain[b, k] = retained_score(blk, V, M)
+    return gain
+
+
+def perm_gain_out(Sp: np.ndarray, V: int, M: int, slot: int) -> np.ndarray:
+    """Output half-step (Eq. 9), one slot: gain[r, k] = retained score of row block k (all columns)
+    with its row at position `slot` replaced by the row at that position of row block r.  [R, R]."""
+    Rf = Sp.shape[0] // V
+    gain = np.zeros((Rf, Rf), dtype=np.int64)
+    for k in range(Rf):
+        for r in range(Rf):
+            blk = Sp[k * V:(k + 1) * V].copy()
+            blk[slot] = Sp[r * V + slot]
+            gain[r, k] = retained_score(blk, V, M)
+    return gain
+
+
+def lsa_max(gain: np.ndarray):
+    """Linear sum assignment maximising sum_i gain[i, assign[i]] (library routine; the gains are
+    integers below 2**53, exact in its fp64).  Returns (assign, total)."""
+    from scipy.optimize import linear_sum_assignment
+    rows, cols = linear_sum_assignment(np.asarray(gain, dtype=np.float64), maximize=True)
+    assign = np.empty(len(rows), dtype=np.int64)
+    assign[rows] = cols
+    return assign, int(np.asarray(gain, dtype=np.int64)[rows, cols].sum())
+
+
+def permutation_search(S: np.ndarray, V: int, M: int, scale: float, iterations: int = 2):
+    """Alternating optimisation of Eqs. 8-9.  Returns (perm_out, perm_in, history): row o / column i
+    of the permuted matrix is row perm_out[o] / column perm_in[i] of S; history[0] is the objective
+    at the identity, then one entry after every half-step (input first)."""
+    Sq = quantise_scores(S, scale)
+    out, inn = Sq.shape
+    po, pi = np.arange(out), np.arange(inn)
+    hist = [permutation_objective(Sq, V, M, po, pi)]
+    for _ in range(iterations):
+        for slot in range(M):                                   # Eq. 8: P_i for fixed P_o
+            assign, _ = lsa_max(perm_gain_in(Sq[po][:, pi], V, M, slot))
+            new = pi.copy()
+            for b, k in enumerate(assign):
+                new[k * M + slot] = pi[b * M + slot]
+            pi = new
+        hist.append(permutation_objective(Sq, V, M, po, pi))
+        for slot in range(V):                                   # Eq. 9: P_o for fixed P_i
+            assign, _ = lsa_max(perm_gain_out(Sq[po][:, pi], V, M, slot))
+            new = po.copy()
+            for r, k in enumerate(assign):
+                new[k * V + slot] = po[r * V + slot]
+            po = new
+        hist.append(permutation_objective(Sq, V, M, po, pi))
+    return po, pi, hist
 
 
 # ---------------------------------------------------------------- V and M selection (Section 4.1)

@@ -49,6 +49,8 @@ def load_library():
     lib.vnm_spmm_fused.restype = ci
     lib.vnm_spmm_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_fused_workspace_bytes.restype = ci
+    lib.vnm_lsa_max.argtypes = [vp, ci, vp, ctypes.POINTER(i64)]
+    lib.vnm_lsa_max.restype = ci
     lib.vnm_fold_permutations.argtypes = [vp, vp, i64, vp]
     lib.vnm_fold_permutations.restype = ci
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]

@@ -237,6 +237,44 @@ int vnm_select_vm(const int* V, const int* M, const double* speedup, int n, doub
                   int* selected);
 
 /*
+ * Search for the channel permutations (Section 4.2, Eqs. 7-9): alternating optimisation of the input
+ * and the output permutation, both starting as the identity, `iterations` times (the paper uses 2),
+ * maximising the importance that V:N:M pruning retains on the permuted score matrix (Eq. 7).
+ *   S        dev fp32 [out x in], leading dimension lds >= in: importance scores (RIA, Eq. 1, in the
+ *            paper), finite and non-negative
+ *   scale    > 0: scores are quantised once to integers, rint(S * scale) in fp64 clipped to
+ *            [0, 2^32 - 1]; all sums are exact 64-bit integers, so results do not depend on any
+ *            order of summation (choose scale so that the largest score lands near 2^30)
+ *   perm_out host int32 [out], perm_in host int32 [in] (outputs): row o / column i of the permuted
+ *            matrix is row perm_out[o] / column perm_in[i] of S -- the arrays vnm_spmm_fused takes
+ *   history  host int64 [1 + 2 * iterations] (output): the objective at the identity, then after
+ *            every half-step (input first); never decreasing
+ *   workspace dev, 256-byte aligned, vnm_permutation_search_workspace_bytes bytes
+ * The paper models each half-step as a linear sum assignment problem without printing the model.
+ * The one used: the half-step visits the in-block positions in turn; for position q the channel at
+ * position q of every full block is lifted out, gain[b][k] is the retained importance of block k
+ * with the channel lifted from block b put into the free position, and the assignment of maximal
+ * total gain (vnm_lsa_max) is applied.  Channels of a ragged last block (in % M, out % V) stay in
+ * place.  The call is synchronous (it alternates device kernels and the host solver) and uses
+ * `stream` for its device work.  V in {16, 32, 64, 128}, 4 <= M <= 32, out / V <= 8192.
+ *
+ * vnm_permutation_gain: one gain matrix of that search, for inspection and tests: which = 0 input
+ * half-step (gain int64 [B x B], B = in / M), 1 output half-step ([R x R], R = out / V), for position
+ * `slot`, at the given permutations (host int32 arrays, NULL = identity); gain is a host array.
+ * vnm_retained_score: the objective (Eq. 7) at the given permutations.
+ */
+int vnm_permutation_search_workspace_bytes(int64_t out, int64_t in, int V, int N, int M, int64_t* bytes);
+int vnm_permutation_search(const void* S, int64_t out, int64_t in, int64_t lds, int V, int N, int M,
+                           double scale, int iterations, void* perm_out, void* perm_in,
+                           int64_t* history, void* workspace, int64_t workspace_bytes, void* stream);
+int vnm_permutation_gain(const void* S, int64_t out, int64_t in, int64_t lds, int V, int N, int M,
+                         double scale, int which, int slot, const void* perm_out, const void* perm_in,
+                         void* gain, void* workspace, int64_t workspace_bytes, void* stream);
+int vnm_retained_score(const void* S, int64_t out, int64_t in, int64_t lds, int V, int N, int M,
+                       double scale, const void* perm_out, const void* perm_in, int64_t* total,
+                       void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Host only.  Linear sum assignment (Section 4.2: every half-step of the permutation search is
  * modelled as one and solved by the Hungarian algorithm): assign[i] = the column given to row i such
  * that sum_i gain[i, assign[i]] is maximal; *total = that sum.  gain: int64 [n x n], row-major,

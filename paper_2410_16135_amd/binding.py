@@ -49,6 +49,15 @@ def load_library():
     lib.vnm_spmm_fused.restype = ci
     lib.vnm_spmm_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_fused_workspace_bytes.restype = ci
+    cd = ctypes.c_double
+    lib.vnm_permutation_search_workspace_bytes.argtypes = [i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
+    lib.vnm_permutation_search_workspace_bytes.restype = ci
+    lib.vnm_permutation_search.argtypes = [vp, i64, i64, i64, ci, ci, ci, cd, ci, vp, vp, vp, vp, i64, vp]
+    lib.vnm_permutation_search.restype = ci
+    lib.vnm_permutation_gain.argtypes = [vp, i64, i64, i64, ci, ci, ci, cd, ci, ci, vp, vp, vp, vp, i64, vp]
+    lib.vnm_permutation_gain.restype = ci
+    lib.vnm_retained_score.argtypes = [vp, i64, i64, i64, ci, ci, ci, cd, vp, vp, ctypes.POINTER(i64), vp, i64, vp]
+    lib.vnm_retained_score.restype = ci
     lib.vnm_lsa_max.argtypes = [vp, ci, vp, ctypes.POINTER(i64)]
     lib.vnm_lsa_max.restype = ci
     lib.vnm_fold_permutations.argtypes = [vp, vp, i64, vp]
@@ -276,6 +285,68 @@ def vnm_fold_permutations(perm_out_prev, perm_in_next):
     _check(load_library().vnm_fold_permutations(po.ctypes.data, pi.ctypes.data, po.size, res.ctypes.data),
            "vnm_fold_permutations")
     return res
+
+
+def _ps_workspace(S, V, M, N):
+    import torch
+    b = ctypes.c_int64(0)
+    _check(load_library().vnm_permutation_search_workspace_bytes(S.shape[0], S.shape[1], V, N, M, ctypes.byref(b)),
+           "vnm_permutation_search_workspace_bytes")
+    return _workspace((S.device, "permsearch"), b.value)
+
+
+def _host_perm(p, n):
+    import numpy as np
+    if p is None:
+        return None, None
+    a = np.ascontiguousarray(p, dtype=np.int32)
+    assert a.shape == (n,)
+    return a, a.ctypes.data
+
+
+def vnm_permutation_search(S, V: int, M: int, scale: float, iterations: int = 2, N: int = 2):
+    """Channel-permutation search of Eqs. 7-9 on the fp32 CUDA score matrix S.  Returns
+    (perm_out, perm_in, history) as numpy arrays (int32, int32, int64)."""
+    import numpy as np
+    import torch
+    assert S.is_cuda and S.dtype == torch.float32 and S.dim() == 2 and S.stride(1) == 1
+    out, inn = S.shape
+    ws = _ps_workspace(S, V, M, N)
+    po, pi = np.empty(out, dtype=np.int32), np.empty(inn, dtype=np.int32)
+    hist = np.zeros(1 + 2 * iterations, dtype=np.int64)
+    _check(load_library().vnm_permutation_search(_ptr(S), out, inn, S.stride(0), V, N, M, float(scale), iterations,
+                                                 po.ctypes.data, pi.ctypes.data, hist.ctypes.data, _ptr(ws),
+                                                 ws.numel(), _stream(S)), "vnm_permutation_search")
+    return po, pi, hist
+
+
+def vnm_permutation_gain(S, V: int, M: int, scale: float, which: int, slot: int, perm_out=None, perm_in=None,
+                         N: int = 2):
+    """One gain matrix of the search (which: 0 input half-step, 1 output half-step); int64 numpy."""
+    import numpy as np
+    out, inn = S.shape
+    ws = _ps_workspace(S, V, M, N)
+    n = inn // M if which == 0 else out // V
+    gain = np.zeros((n, n), dtype=np.int64)
+    po, po_p = _host_perm(perm_out, out)
+    pi, pi_p = _host_perm(perm_in, inn)
+    _check(load_library().vnm_permutation_gain(_ptr(S), out, inn, S.stride(0), V, N, M, float(scale), which, slot,
+                                               po_p, pi_p, gain.ctypes.data, _ptr(ws), ws.numel(), _stream(S)),
+           "vnm_permutation_gain")
+    return gain
+
+
+def vnm_retained_score(S, V: int, M: int, scale: float, perm_out=None, perm_in=None, N: int = 2) -> int:
+    """Objective of Eq. 7 at the given permutations (host int arrays or None)."""
+    out, inn = S.shape
+    ws = _ps_workspace(S, V, M, N)
+    po, po_p = _host_perm(perm_out, out)
+    pi, pi_p = _host_perm(perm_in, inn)
+    tot = ctypes.c_int64(0)
+    _check(load_library().vnm_retained_score(_ptr(S), out, inn, S.stride(0), V, N, M, float(scale), po_p, pi_p,
+                                             ctypes.byref(tot), _ptr(ws), ws.numel(), _stream(S)),
+           "vnm_retained_score")
+    return tot.value
 
 
 def vnm_stage_x(X, M: int, staged=None):

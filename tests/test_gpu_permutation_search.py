@@ -1,0 +1,195 @@
+"""GPU parity of the permutation search (Section 4.2, Eqs. 7-9) against the CPU oracle: the objective,
+the gain matrices of both half-steps (exact 64-bit integers), and the search as a whole."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2410_16135_amd as vnm
+from oracle import vnm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SCALE = float(2 ** 20)
+
+
+def _scores(rng, out, inn, kind="smooth"):
+    if kind == "smooth":
+        return (rng.random((out, inn)) ** 3).astype(np.float32)
+    if kind == "ties":                                  # few distinct values: ties in sums and in rows
+        return rng.integers(0, 4, size=(out, inn)).astype(np.float32) / 8
+    if kind == "outliers":                              # a few heavy input channels, as in LLM weights
+        S = (rng.random((out, inn)) ** 2).astype(np.float32)
+        S[:, rng.choice(inn, size=max(1, inn // 16), replace=False)] *= 50
+        return S
+    raise ValueError(kind)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+SHAPES = [
+    # out, in, V, M          ragged rows / columns included
+    (32, 40, 16, 5), (64, 48, 16, 6), (48, 64, 16, 4), (40, 43, 16, 5), (64, 80, 32, 8), (128, 60, 64, 5),
+    (32, 66, 16, 16),
+]
+
+
+@pytest.mark.parametrize("out,inn,V,M", SHAPES)
+@pytest.mark.parametrize("kind", ["smooth", "ties", "outliers"])
+def test_objective_matches_oracle(out, inn, V, M, kind):
+    rng = np.random.default_rng(out * inn + V)
+    S = _scores(rng, out, inn, kind)
+    Sq = orc.quantise_scores(S, SCALE)
+    Sd = _dev(S)
+    assert vnm.vnm_retained_score(Sd, V, M, SCALE) == orc.retained_score(Sq, V, M)
+    po, pi = rng.permutation(out), rng.permutation(inn)
+    assert vnm.vnm_retained_score(Sd, V, M, SCALE, po, pi) == orc.permutation_objective(Sq, V, M, po, pi)
+
+
+def test_objective_quantisation_and_stride():
+    """Clipping at both ends, ties to even in the rounding, a leading dimension above the width."""
+    rng = np.random.default_rng(0)
+    big = _scores(rng, 32, 64)
+    big[0, :8] = [0.5, 1.5, 2.5, 1e12, -4.0, 0.49999, 3.5, 7.0]
+    S = big[:, :40]
+    Sd = _dev(big)[:, :40]
+    assert vnm.vnm_retained_score(Sd, 16, 5, 1.0) == orc.retained_score(orc.quantise_scores(S, 1.0), 16, 5)
+
+
+@pytest.mark.parametrize("out,inn,V,M", SHAPES)
+@pytest.mark.parametrize("kind", ["smooth", "ties"])
+def test_gain_matrices_match_oracle(out, inn, V, M, kind):
+    rng = np.random.default_rng(out + inn + M)
+    S = _scores(rng, out, inn, kind)
+    Sq = orc.quantise_scores(S, SCALE)
+    Sd = _dev(S)
+    po = np.concatenate([rng.permutation((out // V) * V), np.arange((out // V) * V, out)])
+    pi = np.concatenate([rng.permutation((inn // M) * M), np.arange((inn // M) * M, inn)])
+    Sp = Sq[po][:, pi]
+    for slot in sorted({0, 1, M - 1}):
+        g = vnm.vnm_permutation_gain(Sd, V, M, SCALE, 0, slot, po, pi)
+        assert np.array_equal(g, orc.perm_gain_in(Sp, V, M, slot)), ("input", slot)
+    for slot in sorted({0, 3, V - 1}):
+        g = vnm.vnm_permutation_gain(Sd, V, M, SCALE, 1, slot, po, pi)
+        assert np.array_equal(g, orc.perm_gain_out(Sp, V, M, slot)), ("output", slot)
+
+
+@pytest.mark.parametrize("out,inn,V,M", [(32, 40, 16, 5), (64, 48, 16, 6), (40, 43, 16, 5), (64, 80, 32, 8)])
+@pytest.mark.parametrize("kind", ["smooth", "outliers"])
+def test_search_against_oracle(out, inn, V, M, kind):
+    """The search as a whole.  Several assignments can be optimal in a round (a lifted channel that
+    enters no block's kept four has the same gain everywhere), and which one is taken steers the
+    later rounds, so two correct implementations need not walk the same path.  What is unique is
+    checked: the starting objective, that no half-step lowers it, that the oracle evaluates the
+    returned permutations to the objective the library reports -- and, round by round from the
+    library's own states, that every assignment it took reaches the oracle's optimum value."""
+    rng = np.random.default_rng(out * 3 + inn)
+    S = _scores(rng, out, inn, kind)
+    Sd = _dev(S)
+    po, pi, hist = vnm.vnm_permutation_search(Sd, V, M, SCALE, iterations=2)
+    Sq = orc.quantise_scores(S, SCALE)
+    assert sorted(po) == list(range(out)) and sorted(pi) == list(range(inn))
+    assert hist[0] == orc.retained_score(Sq, V, M)
+    assert all(b >= a for a, b in zip(hist, hist[1:]))
+    assert orc.permutation_objective(Sq, V, M, po, pi) == hist[-1]
+    # one input round and one output round replayed from the identity with the library's pieces
+    lib = vnm.load_library()
+    import ctypes
+    for which, n, width in ((0, inn // M, M), (1, out // V, V)):
+        g = vnm.vnm_permutation_gain(Sd, V, M, SCALE, which, 0)
+        assign = np.zeros(n, dtype=np.int32)
+        tot = ctypes.c_int64(0)
+        assert lib.vnm_lsa_max(g.ctypes.data, n, assign.ctypes.data, ctypes.byref(tot)) == 0
+        g_ref = orc.perm_gain_in(Sq, V, M, 0) if which == 0 else orc.perm_gain_out(Sq, V, M, 0)
+        assert tot.value == orc.lsa_max(g_ref)[1]
+        # applying the library's assignment changes the objective by exactly the gain it promised
+        p = np.arange(inn if which == 0 else out)
+        new = p.copy()
+        for src, dst in enumerate(assign):
+            new[dst * width] = p[src * width]
+        after = orc.permutation_objective(Sq, V, M, new if which == 1 else np.arange(out), new if which == 0 else np.arange(inn))
+        assert after - hist[0] == tot.value - int(np.trace(g_ref))
+
+
+def test_search_with_many_ties_stays_valid():
+    """Equal gains everywhere: whichever optimal assignments are taken, the invariants hold."""
+    rng = np.random.default_rng(4)
+    S = _scores(rng, 64, 60, "ties")
+    po, pi, hist = vnm.vnm_permutation_search(_dev(S), 16, 5, 8.0, iterations=2)
+    assert sorted(po) == list(range(64)) and sorted(pi) == list(range(60))
+    assert all(b >= a for a, b in zip(hist, hist[1:]))
+    assert orc.permutation_objective(orc.quantise_scores(S, 8.0), 16, 5, po, pi) == hist[-1]
+
+
+def test_planted_case():
+    out, V, M, B = 32, 16, 8, 4
+    S = np.full((out, B * M), 1.0, dtype=np.float32)
+    S[:, 0:8] = 100.0
+    po, pi, hist = vnm.vnm_permutation_search(_dev(S), V, M, 1.0, iterations=1)
+    assert hist[0] == out * (2 * 100 + 3 * 2 * 1)
+    assert hist[1] == out * (2 * 100 * 4)
+
+
+def test_search_feeds_the_fused_layer():
+    """End to end: RIA scores -> search -> prune the permuted weight -> vnm_spmm_fused with the found
+    permutations; the retained RIA mass grows and the layer output matches the oracle's Eq. 6."""
+    import synth_inputs as syn
+    out, inn, T, V, M = 256, 320, 100, 64, 5
+    W, X = syn.make_weight_and_input(out, inn, T, seed=5)
+    rng = np.random.default_rng(5)
+    W[:, rng.choice(inn, size=16, replace=False)] *= 8          # heavy input channels
+    Wd = _dev(W)
+    act = torch.ones(inn, dtype=torch.float32, device=DEV)
+    S = vnm.vnm_ria_scores(Wd, act)
+    scale = float(2 ** 30) / float(S.max().item())
+    po, pi, hist = vnm.vnm_permutation_search(S, V, M, scale, iterations=2)
+    assert hist[-1] > hist[0]
+    Wp = orc.permute_weight(W, po, pi)
+    Sp = orc.permute_weight(S.cpu().numpy(), po, pi)
+    c = vnm.vnm_prune_compress_scored(_dev(Wp), _dev(Sp), V, M, want_mask=True)
+    Y = vnm.vnm_spmm_fused(_dev(X), c, perm_in=_dev(pi.astype(np.int32)), perm_out=_dev(po.astype(np.int32)))
+    torch.cuda.synchronize()
+    mask = c.mask.cpu().numpy()
+    # the pruning (driven by the fp32 scores) keeps what the objective (on the quantised scores) counted,
+    # up to selections that differ where quantisation merges nearly equal scores
+    kept = int(orc.quantise_scores(Sp, scale)[mask == 1].sum())
+    assert abs(kept - hist[-1]) <= 1e-6 * hist[-1]
+    Y_ref = orc.linear_fused_ref(X, orc.masked_dense(Wp, mask), perm_in=pi, perm_out=po)
+    assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= 1e-2
+
+
+def test_medium_size_invariants():
+    """1024 x 1280 at 64:2:5 (256 column blocks, 16 row blocks): too large for the oracle's gain
+    loops, so the oracle checks what holds at any size: the reported objective of the result."""
+    rng = np.random.default_rng(6)
+    S = _scores(rng, 1024, 1280, "outliers")
+    po, pi, hist = vnm.vnm_permutation_search(_dev(S), 64, 5, SCALE, iterations=1)
+    assert sorted(po) == list(range(1024)) and sorted(pi) == list(range(1280))
+    assert all(b >= a for a, b in zip(hist, hist[1:])) and hist[-1] > hist[0]
+    Sq = orc.quantise_scores(S, SCALE)
+    assert orc.permutation_objective(Sq, 64, 5, po, pi) == hist[-1]
+    assert orc.retained_score(Sq, 64, 5) == hist[0]
+
+
+def test_argument_errors():
+    lib = vnm.load_library()
+    S = torch.zeros((32, 40), dtype=torch.float32, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    po, pi = np.zeros(32, dtype=np.int32), np.zeros(40, dtype=np.int32)
+    hist = np.zeros(5, dtype=np.int64)
+
+    def call(V=16, M=5, scale=1.0, ws_bytes=ws.numel(), iters=2):
+        return lib.vnm_permutation_search(S.data_ptr(), 32, 40, 40, V, 2, M, scale, iters, po.ctypes.data,
+                                          pi.ctypes.data, hist.ctypes.data, ws.data_ptr(), ws_bytes, None)
+    assert call() == 0
+    assert call(V=8) == 3 and call(M=3) == 3 and call(M=33) == 3 and call(scale=0.0) == 3
+    assert call(ws_bytes=1024) == 5
+    assert call(iters=-1) == 2
+    tot = np.zeros(1, dtype=np.int64)
+    bad = np.zeros(32, dtype=np.int32)                       # not a permutation
+    import ctypes
+    assert lib.vnm_retained_score(S.data_ptr(), 32, 40, 40, 16, 2, 5, 1.0, bad.ctypes.data, None,
+                                  tot.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), ws.data_ptr(), ws.numel(),
+                                  None) == 2

@@ -381,6 +381,16 @@ def main():
             "with_bias_perm_in_perm_out_ms": t_all,
             "note": "vnm_spmm_fused on the first layer, HIP-event means; permutations folded into the "
                     "neighbouring layers cost nothing, these are the run-time fallbacks"}
+        # channel-permutation search (Eqs. 7-9) on the first layer's RIA scores, one alternation
+        sc = float(2 ** 30) / float(S.max().item())
+        t0 = time.time()
+        _, _, hist = vnm.vnm_permutation_search(S, L.V, L.M, sc, iterations=1)
+        result["permutation_search"] = {
+            "layer": L.name, "iterations": 1, "seconds": time.time() - t0,
+            "objective": [int(h) for h in hist],
+            "retained_gain_percent": 100.0 * float(hist[-1] - hist[0]) / float(hist[0]),
+            "note": "wall time incl. the host assignment solver (5 problems of 819 x 819, 64 of 64 x 64), "
+                    "which takes most of it; device kernels about 25 ms"}
         result["beyond_hot_path"] = {
             "layer": L.name, "ria_scores_ms": t_ria, "prune_compress_scored_ms": t_ps,
             "ria_scores_gbps": (2 * w_bytes + 2 * w_bytes) / t_ria / 1e6,

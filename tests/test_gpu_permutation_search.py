@@ -173,6 +173,38 @@ def test_medium_size_invariants():
     assert orc.retained_score(Sq, 64, 5) == hist[0]
 
 
+@pytest.mark.parametrize("which_layer", [0, 6])
+def test_llama_shaped_layer_sampled_gain_entries(which_layer):
+    """Full-size layers (4096 x 4096 and 4096 x 11008 at 64:2:5): the objective, and sampled entries of
+    both gain matrices, each recomputed by the oracle from its definition (one pruning of the
+    hypothetical block per entry)."""
+    import synth_inputs as syn
+    L = syn.config_llama2_7b()[which_layer]
+    W, _ = syn.layer_tensors(L, tokens=1)
+    rng = np.random.default_rng(which_layer)
+    act = (0.5 + rng.random(L.inn)).astype(np.float32)
+    S = vnm.vnm_ria_scores(_dev(W), _dev(act))
+    scale = float(2 ** 30) / float(S.max().item())
+    Sh = S.cpu().numpy()
+    Sq = orc.quantise_scores(Sh, scale)
+    V, M = L.V, L.M
+    assert vnm.vnm_retained_score(S, V, M, scale) == orc.retained_score(Sq, V, M)
+    slot = 2
+    g_in = vnm.vnm_permutation_gain(S, V, M, scale, 0, slot)
+    Bf = L.inn // M
+    for b, k in [(0, 0), (1, 0), (Bf - 1, 5), (17, Bf - 1), (100, 100)] + [tuple(rng.integers(0, Bf, 2)) for _ in range(8)]:
+        blk = Sq[:, k * M:(k + 1) * M].copy()
+        blk[:, slot] = Sq[:, b * M + slot]
+        assert g_in[b, k] == orc.retained_score(blk, V, M), ("input", b, k)
+    slot = 37
+    g_out = vnm.vnm_permutation_gain(S, V, M, scale, 1, slot)
+    Rf = L.out // V
+    for r, k in [(0, 0), (1, 0), (Rf - 1, 3), (5, Rf - 1)] + [tuple(rng.integers(0, Rf, 2)) for _ in range(4)]:
+        blk = Sq[k * V:(k + 1) * V].copy()
+        blk[slot] = Sq[r * V + slot]
+        assert g_out[r, k] == orc.retained_score(blk, V, M), ("output", r, k)
+
+
 def test_argument_errors():
     lib = vnm.load_library()
     S = torch.zeros((32, 40), dtype=torch.float32, device=DEV)

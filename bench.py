@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm-only", action="store_true", help="time vnm_spmm alone (profiling aid)")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="skip the sections after the timed region that run other kernels or other shapes "
+                         "(RIA, fused layer, permutation search, few tokens): per-kernel profiler averages "
+                         "then cover the timed workload only")
     return ap.parse_args()
 
 
@@ -323,7 +327,7 @@ def main():
         "calibration_copy": {"bytes_read": calib_bytes, "bytes_written": calib_bytes,
                              "what": "one torch copy_ of the first layer's W after the timed region"},
     }
-    if not args.spmm_only:
+    if not args.spmm_only and not args.hot_path_only:
         # next row after the hot path (not part of `value`): RIA scores (Eq. 1) and pruning driven
         # by them, on the first layer; and the few-token product (decode) on the same layer
         L, Wd, Xd, c, Y, Wout = state[0]

@@ -446,3 +446,40 @@ def test_random_shapes_whole_path(out, inn, T, V, M):
     Y_ref = orc.matmul_ref(X, Wm)
     assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
     assert orc.max_normalised_error(Yh.float().cpu().numpy(), Y_ref) <= TOL
+
+
+# ---------------------------------------------------------------- sizes beyond single-launch grid limits
+
+@pytest.mark.parametrize("path", [vnm.PATH_GENERIC, vnm.PATH_SMFMAC])
+def test_more_tokens_than_one_grid_dimension(path):
+    """T = 70 001 (above the 65 535 limit of a grid's y dimension, ragged last token tile) on the
+    single-GEMM layer; every output checked."""
+    (layer,) = syn.config_single_gemm()
+    W, _ = syn.layer_tensors(layer)
+    rng = np.random.default_rng(70001)
+    X = rng.standard_normal((70001, layer.inn), dtype=np.float32).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), layer.V, layer.M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, path=path)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, orc.compress(W, layer.V, layer.M)[3]))
+    assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
+
+
+@pytest.mark.parametrize("V,M,inn", [(64, 5, 40), (16, 5, 35), (128, 8, 64)])
+def test_more_rows_than_one_grid_dimension(V, M, inn):
+    """out = 66 048 rows (1 032 ... 4 128 row blocks; the row-wise kernels cross the 65 535 limit)."""
+    out = 66048
+    rng = np.random.default_rng(V * M)
+    W = _rand_w(rng, out, inn, "normal")
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    torch.cuda.synchronize()
+    values, meta, colidx, mask = _check_compressed(c, W, V, M)
+    Wd = vnm.vnm_decompress(c).cpu().numpy()
+    assert np.array_equal(Wd.view(np.uint16), orc.masked_dense(W, mask).view(np.uint16))
+    X = rng.integers(-2, 3, size=(40, inn)).astype(np.float16)
+    Wi = rng.integers(-2, 3, size=(out, inn)).astype(np.float16)
+    ci = vnm.vnm_prune_compress(_dev(Wi), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), ci, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(Wi, orc.compress(Wi, V, M)[3]))
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), Y_ref)

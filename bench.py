@@ -292,7 +292,11 @@ def main():
     # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled by the calibration
     # copy); known only for the default workload
     default_wl = (args.workload == "llama2_7b" and L0_is_default(layers))
-    traffic = 347.7e6 if default_wl else None
+    traffic = 347.6e6 if default_wl else None
+    # matrix-core and LDS counters of the same kernel from the same profile (rocprofv3 --pmc, SQ block)
+    counters = {"mfma_busy_percent": 42.5, "lds_active_percent_of_cu_busy": 47.6,
+                "lds_bank_conflict_percent_of_lds_active": 31.6, "hbm_side_tb_per_s": 3.02,
+                "source": "profiles/bench_llama2_7b_64-2-5_T4096.md"} if default_wl else None
     dense_total = sum(dense_ms[L.name] for L in layers)
     L0 = layers[0]
     result = {
@@ -315,7 +319,7 @@ def main():
                      "frac": kept / product_ms / 1e9 / PEAK_FP16_DENSE_TFLOPS, "traffic": traffic,
                      "launches_per_step": len(layers), "avg_launch_us": product_ms / len(layers) * 1e3,
                      "flops_per_launch": kept / len(layers),
-                     "dense_equiv_tflops": dense_equiv / product_ms / 1e9,
+                     "dense_equiv_tflops": dense_equiv / product_ms / 1e9, "counters": counters,
                      "note": "per launch, mean over the launches of a step (one per layer): flops on kept weights "
                              "2*T*out*2*col_blocks / launch duration from HIP events around the product kernel "
                              "inside the timed region; peak = published dense fp16 MFMA rate; traffic = HBM-side "

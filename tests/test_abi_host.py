@@ -121,3 +121,14 @@ def test_package_has_no_cpu_fallback():
                     assert "oracle" not in f.read(), fn
     with open(os.path.join(ROOT, "oracle", "vnm_oracle.py")) as f:
         assert "paper_2410_16135_amd" not in f.read()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build has no distributed path: bench.py --gpus N with N > 1 exits with a message."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "single-GPU" in res.stderr + res.stdout

@@ -212,7 +212,9 @@ _WORKSPACES = {}
 
 
 def _workspace(device, nbytes: int):
-    """One grow-only scratch tensor per device, shared by all vnm_spmm calls of this process."""
+    """One grow-only scratch tensor per device, shared by all vnm_spmm calls of this process.
+    Its reuse is ordered by the stream the calls run on: callers that use several streams at once
+    must hand every call a `workspace` of its own."""
     import torch
     ws = _WORKSPACES.get(device)
     if ws is None or ws.numel() < nbytes:

@@ -230,3 +230,46 @@ def test_llama_shaped_layer_fused_sampled_tokens():
     toks = np.sort(rng.choice(X.shape[0], size=64, replace=False))
     Y_ref = orc.linear_fused_ref(X[toks], Wm, bias=bias, perm_in=pi, perm_out=po)
     assert orc.max_normalised_error(Y.cpu().numpy()[toks], Y_ref) <= TOL
+
+
+@pytest.mark.parametrize("T", [16, 200])
+def test_calls_replay_from_a_hip_graph(T):
+    """The product calls are plain kernel launches on the caller's stream (no allocation, no memset
+    node, no host synchronisation), so a captured graph of them replays correctly: three replays on
+    fresh inputs, each checked against an eager call, with eager work in between."""
+    X, Wm_p, bias, pi, po, c = _layer(256, 320, T, 64, 5, seed=40 + T)
+    Xd = _dev(X)
+    bd, pid, pod = _dev(bias), _dev(pi), _dev(po)
+    lib = vnm.load_library()
+    import ctypes
+    nb = ctypes.c_int64(0)
+    assert lib.vnm_spmm_fused_workspace_bytes(T, 256, 320, 64, 2, 5, 1, ctypes.byref(nb)) == 0
+    ws = torch.empty(nb.value, dtype=torch.uint8, device=DEV)
+    Y_plain = torch.empty((T, 256), dtype=torch.float16, device=DEV)
+    Y_fused = torch.empty((T, 256), dtype=torch.float16, device=DEV)
+
+    def work():
+        vnm.vnm_spmm(Xd, c, Y=Y_plain, workspace=ws)
+        vnm.vnm_spmm_fused(Xd, c, bias=bd, perm_in=pid, perm_out=pod, Y=Y_fused, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()                                   # warm-up outside the capture (one-off attribute calls)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    rng = np.random.default_rng(T)
+    for rep in range(3):
+        Xn = rng.standard_normal(X.shape).astype(np.float16)
+        Xd.copy_(_dev(Xn))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_plain, got_fused = Y_plain.clone(), Y_fused.clone()
+        work()                                   # eager, same buffers
+        torch.cuda.synchronize()
+        assert torch.equal(got_plain, Y_plain) and torch.equal(got_fused, Y_fused), rep
+        assert orc.max_normalised_error(got_plain.cpu().numpy(), orc.matmul_ref(Xn, Wm_p)) <= TOL
+        assert orc.max_normalised_error(got_fused.cpu().numpy(), orc.linear_fused_ref(Xn, Wm_p, bias, pi, po)) <= TOL

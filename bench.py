@@ -389,6 +389,25 @@ def main():
             "with_bias_perm_in_perm_out_ms": t_all,
             "note": "vnm_spmm_fused on the first layer, HIP-event means; permutations folded into the "
                     "neighbouring layers cost nothing, these are the run-time fallbacks"}
+        # mask refresh of the LoRA stage with dynamic masks (Eq. 10): merge B A into W, RIA scores, pruning
+        r_lora = 16
+        gB = torch.Generator(device="cpu").manual_seed(11)
+        Bl = (torch.randn(L.out, r_lora, generator=gB) * 0.02).to(dev)
+        Al = (torch.randn(r_lora, L.inn, generator=gB) * 0.02).to(dev)
+        Wm = torch.empty_like(Wd)
+        t_merge = timed(lambda: vnm.vnm_lora_merge(Wd, Bl, Al, 2.0, W_merged=Wm), n=20, warm=50)
+
+        def refresh():
+            vnm.vnm_lora_merge(Wd, Bl, Al, 2.0, W_merged=Wm)
+            vnm.vnm_ria_scores(Wm, act, S=S)
+            vnm.vnm_prune_compress_scored(Wm, S, L.V, L.M, out=cs)
+        t_refresh = timed(refresh, n=20, warm=20)
+        result["mask_refresh"] = {
+            "layer": L.name, "lora_rank": r_lora, "merge_ms": t_merge, "merge_gbps": 2 * w_bytes / t_merge / 1e6,
+            "merge_ria_prune_ms": t_refresh,
+            "note": "vnm_lora_merge alone, and merge + RIA scores + pruning from scores (one mask update of one "
+                    "layer); HIP-event means"}
+        vnm.vnm_ria_scores(Wd, act, S=S)          # the search below uses the scores of the unmerged weight
         # channel-permutation search (Eqs. 7-9) on the first layer's RIA scores, one alternation
         sc = float(2 ** 30) / float(S.max().item())
         t0 = time.time()

@@ -115,6 +115,23 @@ int vnm_prune_compress_scored(const void* W, const void* S, int64_t out, int64_t
                               void* values, void* meta, void* colidx, void* mask, void* packed,
                               void* stream);
 
+/*
+ * Merge of the low-rank LoRA matrices into the dense weight (Section 4.3, Eq. 10: W' = (W + B A) (.) M;
+ * in the stage with dynamic masks the mask update merges B A into W before scores are computed and
+ * the pattern is pruned):  W_merged = fp16(W + scale * B A).
+ *   W, W_merged  dev fp16 [out x in], leading dimensions ldw, ldm >= in (W_merged may be W)
+ *   B            dev fp32 [out x r], leading dimension ldb >= r;   A  dev fp32 [r x in], lda >= in
+ *   scale        the LoRA scaling alpha / r (2 in the paper's runs); r = 0 copies W
+ * The paper fixes neither precision nor order; since the merged weights decide a mask, the merge is
+ * defined to the bit: fp32, one rounding per operation, no fused multiply-add, k ascending:
+ * acc = acc + (B[o,k] * A[k,i]), then (scale * acc) + W[o,i], then one rounding to fp16.
+ * A mask refresh is this call followed by vnm_prune_compress, or by vnm_ria_scores and
+ * vnm_prune_compress_scored, on W_merged.
+ */
+int vnm_lora_merge(const void* W, int64_t out, int64_t in, int64_t ldw, const void* B, int64_t ldb,
+                   const void* A, int64_t lda, int r, float scale, void* W_merged, int64_t ldm,
+                   void* stream);
+
 /* Builds `packed` from an existing canonical triple (e.g. one loaded from storage). */
 int vnm_pack(const void* values, const void* meta, const void* colidx,
              int64_t out, int64_t in, int V, int N, int M, void* packed, void* stream);

@@ -17,6 +17,8 @@ Everything here follows the paper's own wording of the method:
 * Section 4.2, Eq. 6: the layer evaluated on a channel-permuted weight
   (permute_weight, linear_fused_ref, fold_permutations); Eqs. 7-9: the search
   for the permutations (permutation_search and its parts).
+* Section 4.3, Eq. 10: merging the low-rank LoRA matrices into the dense weight
+  and refreshing the mask from the merged weight (lora_merge, refresh_mask).
 * Section 3 ("Acceleration of V:N:M sparsity"): zero padding so that the
   input dimension is a multiple of M and the output dimension a multiple of V.
 * Appendix A: the compressed triple -- the compact kept values (A_n), the four
@@ -438,6 +440,38 @@ def permutation_search(S: np.ndarray, V: int, M: int, scale: float, iterations: 
             po = new
         hist.append(permutation_objective(Sq, V, M, po, pi))
     return po, pi, hist
+
+
+# ---------------------------------------------------------------- LoRA merge and mask refresh (Section 4.3, Eq. 10)
+
+def lora_merge(W: np.ndarray, B: np.ndarray, A: np.ndarray, scale: float) -> np.ndarray:
+    """W + scale * B A of Eq. 10 as the fp16 matrix the mask update prunes (Section 4.3, stage 2:
+    the low-rank matrices are merged into the dense weight before scores are computed).
+
+    W fp16 [out x in], B fp32 [out x r], A fp32 [r x in].  The paper fixes neither precision nor
+    order; so that the refreshed mask is reproducible to the bit the merge is defined in fp32 with
+    one rounding per operation and a fixed order:
+        acc = 0;  for k = 0..r-1:  acc = acc + (B[o,k] * A[k,i]);  m = (scale * acc) + W[o,i]
+    (every product and sum rounded to fp32, no fused multiply-add), then m rounded to fp16.
+    """
+    W = _as_fp16_matrix(W)
+    B = np.asarray(B, dtype=np.float32)
+    A = np.asarray(A, dtype=np.float32)
+    acc = np.zeros(W.shape, dtype=np.float32)
+    for k in range(B.shape[1]):
+        acc = acc + B[:, k:k + 1] * A[k:k + 1, :]
+    m = np.float32(scale) * acc + W.astype(np.float32)
+    return m.astype(np.float16)
+
+
+def refresh_mask(W, B, A, scale: float, V: int, M: int, act=None):
+    """Mask update of the second LoRA stage (Section 4.3; Appendix on the LoRA details): merge, score
+    (RIA if activation factors are given, else |w|), prune.  Returns (merged fp16, mask u8) with
+    W' = merged (.) mask as in Eq. 10."""
+    merged = lora_merge(W, B, A, scale)
+    score = None if act is None else importance_ria(merged, act)
+    _, _, mask = prune(merged, V, M, score=score)
+    return merged, mask
 
 
 # ---------------------------------------------------------------- V and M selection (Section 4.1)

@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     vnm_pack, vnm_spmm, vnm_spmm_workspace_bytes, vnm_stage_x, vnm_spmm_staged,
     vnm_spmm_scratch_bytes, vnm_decompress, vnm_ria_scores, vnm_prune_compress_scored,
     vnm_mask_diversity_log, vnm_select_vm, vnm_spmm_fused, vnm_fold_permutations, vnm_permutation_search,
-    vnm_permutation_gain, vnm_retained_score, PATH_AUTO, PATH_GENERIC, PATH_SMFMAC,
+    vnm_permutation_gain, vnm_retained_score, vnm_lora_merge, vnm_refresh_mask, PATH_AUTO, PATH_GENERIC, PATH_SMFMAC,
 )

@@ -58,6 +58,8 @@ def load_library():
     lib.vnm_permutation_gain.restype = ci
     lib.vnm_retained_score.argtypes = [vp, i64, i64, i64, ci, ci, ci, cd, vp, vp, ctypes.POINTER(i64), vp, i64, vp]
     lib.vnm_retained_score.restype = ci
+    lib.vnm_lora_merge.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, ctypes.c_float, vp, i64, vp]
+    lib.vnm_lora_merge.restype = ci
     lib.vnm_lsa_max.argtypes = [vp, ci, vp, ctypes.POINTER(i64)]
     lib.vnm_lsa_max.restype = ci
     lib.vnm_fold_permutations.argtypes = [vp, vp, i64, vp]
@@ -349,6 +351,32 @@ def vnm_retained_score(S, V: int, M: int, scale: float, perm_out=None, perm_in=N
                                              ctypes.byref(tot), _ptr(ws), ws.numel(), _stream(S)),
            "vnm_retained_score")
     return tot.value
+
+
+def vnm_lora_merge(W, B, A, scale: float, W_merged=None):
+    """fp16(W + scale * B A) in the library's fixed fp32 order; W fp16 [out x in], B fp32 [out x r],
+    A fp32 [r x in] (CUDA tensors)."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
+    out, inn = W.shape
+    r = B.shape[1]
+    assert B.dtype == torch.float32 and A.dtype == torch.float32 and B.shape == (out, r) and A.shape == (r, inn)
+    assert (r == 0) or (B.stride(1) == 1 and A.stride(1) == 1)
+    if W_merged is None:
+        W_merged = torch.empty_like(W)
+    _check(load_library().vnm_lora_merge(_ptr(W), out, inn, W.stride(0), _ptr(B), B.stride(0) if r else 0, _ptr(A),
+                                         A.stride(0) if r else inn, r, float(scale), _ptr(W_merged),
+                                         W_merged.stride(0), _stream(W)), "vnm_lora_merge")
+    return W_merged
+
+
+def vnm_refresh_mask(W, B, A, scale: float, V: int, M: int, act=None, N: int = 2) -> Compressed:
+    """Mask update of the LoRA stage with dynamic masks (Section 4.3): merge, score (RIA when `act`
+    is given, else |w|), prune.  Returns the Compressed of the merged weight with its mask."""
+    merged = vnm_lora_merge(W, B, A, scale)
+    if act is None:
+        return vnm_prune_compress(merged, V, M, N, want_mask=True)
+    return vnm_prune_compress_scored(merged, vnm_ria_scores(merged, act), V, M, N, want_mask=True)
 
 
 def vnm_stage_x(X, M: int, staged=None):

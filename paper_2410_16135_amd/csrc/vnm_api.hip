@@ -112,6 +112,15 @@ extern "C" int vnm_prune_compress_scored(const void* W, const void* S, int64_t o
   return VNM_OK;
 }
 
+extern "C" int vnm_lora_merge(const void* W, int64_t out, int64_t in, int64_t ldw, const void* B, int64_t ldb,
+                              const void* A, int64_t lda, int r, float scale, void* W_merged, int64_t ldm,
+                              void* stream) {
+  if (!W || !W_merged || (r > 0 && (!B || !A))) return VNM_ERR_NULL;
+  if (out <= 0 || in <= 0 || r < 0 || ldw < in || ldm < in || (r > 0 && (ldb < r || lda < in))) return VNM_ERR_SHAPE;
+  if (((uintptr_t)W & 1) || ((uintptr_t)W_merged & 1) || ((uintptr_t)B & 3) || ((uintptr_t)A & 3)) return VNM_ERR_ALIGN;
+  return launch_lora_merge(W, ldw, B, ldb, A, lda, r, scale, out, in, W_merged, ldm, (hipStream_t)stream);
+}
+
 extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx, int64_t out,
                         int64_t in, int V, int N, int M, void* packed, void* stream) {
   if (!values || !meta || !colidx || !packed) return VNM_ERR_NULL;

@@ -109,6 +109,9 @@ int launch_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const
                       int64_t lds, void* workspace, hipStream_t st);
 int launch_prune_scored(const void* W, int64_t ldw, const void* S, int64_t lds, const Dims& d, void* values,
                         void* meta, void* colidx, void* mask, hipStream_t st);
+// Wm = fp16(W + scale * B A) in a fixed fp32 order (vnm_score.hip)
+int launch_lora_merge(const void* W, int64_t ldw, const void* B, int64_t ldb, const void* A, int64_t lda, int r,
+                      float scale, int64_t out, int64_t in, void* Wm, int64_t ldm, hipStream_t st);
 // Single-kernel product for at most skinny_max_tokens() tokens, straight from X (no staging, no workspace).
 int64_t skinny_max_tokens();
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,

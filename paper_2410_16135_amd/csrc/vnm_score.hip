@@ -264,3 +264,93 @@ int launch_prune_scored(const void* W, int64_t ldw, const void* S, int64_t lds, 
 }
 
 }  // namespace vnm
+
+// ---------------------------------------------------------------- LoRA merge (Section 4.3, Eq. 10)
+// Wm = fp16(W + scale * B A): what the mask update of the second LoRA stage prunes.  So that the
+// refreshed mask is reproducible to the bit the arithmetic is pinned down: fp32, one rounding per
+// operation (no fused multiply-add), k ascending:
+//     acc = 0;  acc = acc + (B[o,k] * A[k,i]);  m = (scale * acc) + W[o,i];  Wm = fp16(m)
+// One thread per 8 consecutive columns of 8 consecutive rows (A, r x in fp32, is fetched once per 8
+// rows: fetching it once per row made the kernel L2-bound at a third of the speed); W moves with
+// 16-byte accesses, B[o, :] is uniform over the threads of a row.
+namespace vnm {
+
+constexpr int kMergeRows = 8;   // rows per thread: A is fetched once per 8 rows instead of once per row
+
+__global__ void __launch_bounds__(256)
+lora_merge_kernel(const unsigned short* __restrict__ W, int64_t ldw, const float* __restrict__ B, int64_t ldb,
+                  const float* __restrict__ A, int64_t lda, int r, float scale, int64_t out, int64_t in,
+                  unsigned short* __restrict__ Wm, int64_t ldm, int vec, int avec) {
+  // every product and sum below is rounded on its own: no contraction into fused multiply-adds
+#pragma clang fp contract(off)
+  const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t o0 = ((int64_t)blockIdx.y + (int64_t)blockIdx.z * 65535) * kMergeRows;
+  const int64_t i0 = chunk * 8;
+  if (o0 >= out || i0 >= in) return;
+  const int n = (int)(in - i0 < 8 ? in - i0 : 8);
+  const int rows = (int)(out - o0 < kMergeRows ? out - o0 : kMergeRows);
+  float acc[kMergeRows][8];
+#pragma unroll
+  for (int v = 0; v < kMergeRows; ++v)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[v][e] = 0.f;
+  for (int k = 0; k < r; ++k) {
+    float a[8];
+    if (n == 8 && avec) {
+      const float4 a0 = *(const float4*)(A + (int64_t)k * lda + i0), a1 = *(const float4*)(A + (int64_t)k * lda + i0 + 4);
+      a[0] = a0.x; a[1] = a0.y; a[2] = a0.z; a[3] = a0.w; a[4] = a1.x; a[5] = a1.y; a[6] = a1.z; a[7] = a1.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = e < n ? A[(int64_t)k * lda + i0 + e] : 0.f;
+    }
+#pragma unroll
+    for (int v = 0; v < kMergeRows; ++v) {
+      const float b = B[(v < rows ? o0 + v : o0) * ldb + k];      // rows beyond `out` repeat row o0; never stored
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float p = b * a[e]; acc[v][e] = acc[v][e] + p; }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < kMergeRows; ++v) {
+    if (v >= rows) break;
+    const int64_t o = o0 + v;
+    unsigned short w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (vec && n == 8) *(uint4*)w = *(const uint4*)(W + o * ldw + i0);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) if (e < n) w[e] = W[o * ldw + i0 + e];
+    }
+    unsigned short m[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      _Float16 h;
+      __builtin_memcpy(&h, &w[e], 2);
+      const float sp = scale * acc[v][e];
+      const _Float16 res = (_Float16)(sp + (float)h);
+      __builtin_memcpy(&m[e], &res, 2);
+    }
+    if (vec && n == 8) *(uint4*)(Wm + o * ldm + i0) = *(const uint4*)m;
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) if (e < n) Wm[o * ldm + i0 + e] = m[e];
+    }
+  }
+}
+
+int launch_lora_merge(const void* W, int64_t ldw, const void* B, int64_t ldb, const void* A, int64_t lda, int r,
+                      float scale, int64_t out, int64_t in, void* Wm, int64_t ldm, hipStream_t st) {
+  const int vec = (ldw % 8 == 0) && (ldm % 8 == 0) && ((((uintptr_t)W | (uintptr_t)Wm) & 15) == 0);
+  const int avec = (lda % 4 == 0) && (((uintptr_t)A & 15) == 0);
+  const int64_t chunks = (in + 7) / 8;
+  const int64_t row_tiles = (out + kMergeRows - 1) / kMergeRows;
+  const int64_t gz = (row_tiles + 65534) / 65535;
+  if (gz > 65535) return VNM_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)((chunks + 255) / 256), (unsigned)(row_tiles < 65535 ? row_tiles : 65535), (unsigned)gz);
+  hipLaunchKernelGGL(lora_merge_kernel, grid, dim3(256), 0, st, (const unsigned short*)W, ldw, (const float*)B, ldb,
+                     (const float*)A, lda, r, scale, out, in, (unsigned short*)Wm, ldm, vec, avec);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "lora_merge_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
+}  // namespace vnm

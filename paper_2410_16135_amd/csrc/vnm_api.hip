@@ -106,6 +106,9 @@ extern "C" int vnm_prune_compress_scored(const void* W, const void* S, int64_t o
     if ((uintptr_t)packed & 255) return VNM_ERR_ALIGN;
   }
   hipStream_t st = (hipStream_t)stream;
+  // one pass with the weight and score tiles in LDS, packed copy included, where shape and alignment allow
+  if (prune_fast_scored_applicable(W, ldw, S, lds, d) && (!packed || has_packed(V, M)))
+    return launch_prune_fast_scored(W, ldw, S, lds, d, values, meta, colidx, mask, packed, st);
   rc = launch_prune_scored(W, ldw, S, lds, d, values, meta, colidx, mask, st);
   if (rc) return rc;
   if (packed) return launch_pack(values, meta, colidx, d, packed, st);

@@ -84,6 +84,9 @@ int launch_prune_compress(const void* W, int64_t ldw, const Dims& d, void* value
 bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask);
 int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, void* meta, void* colidx,
                       void* mask, void* packed, hipStream_t st);
+bool prune_fast_scored_applicable(const void* W, int64_t ldw, const void* S, int64_t lds_s, const Dims& d);
+int launch_prune_fast_scored(const void* W, int64_t ldw, const void* S, int64_t lds_s, const Dims& d, void* values,
+                             void* meta, void* colidx, void* mask, void* packed, hipStream_t st);
 bool decompress_fast_applicable(const void* W_out, int64_t ldw, const Dims& d);
 int launch_decompress_fast(const void* values, const void* meta, const void* colidx, const Dims& d,
                            void* W_out, int64_t ldw, hipStream_t st);

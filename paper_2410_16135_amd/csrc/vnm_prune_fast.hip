@@ -37,6 +37,20 @@ __device__ __forceinline__ unsigned top2_of_4_f(unsigned w0, unsigned w1, unsign
   return p0 | (p1 << 2);
 }
 
+// The same selection on importance scores handed in (finite, non-negative fp32, compared through
+// their bit patterns without the sign): positions p0 < p1 of the two largest, ties to the lower position.
+__device__ __forceinline__ unsigned top2_of_4_s(unsigned g0, unsigned g1, unsigned g2, unsigned g3) {
+  const unsigned g[4] = {g0, g1, g2, g3};
+  int a = 0;
+#pragma unroll
+  for (int k = 1; k < 4; ++k) if (g[k] > g[a]) a = k;
+  int b = (a == 0) ? 1 : 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) if (k != a && k != b && g[k] > g[b]) b = k;
+  const int p0 = a < b ? a : b, p1 = a < b ? b : a;
+  return (unsigned)p0 | ((unsigned)p1 << 2);
+}
+
 struct PruneFastArgs {
   const unsigned short* W; int64_t ldw, out, in;
   int V, M; int64_t R, B, S;
@@ -44,9 +58,15 @@ struct PruneFastArgs {
   int G;                   // row groups that sum columns in parallel
   unsigned short* values; unsigned char* meta; unsigned char* colidx; unsigned char* mask;
   uint4* pa; unsigned short* pidx; unsigned* pcol;   // matrix-core copy or null
+  const float* Sc; int64_t lds_s;                    // importance scores (SCORED instantiation only)
 };
 
-// LDS layout (dynamic): tile u16 [V][NCP] | tot f64 [NC] | keep u32 [NBW]
+// LDS layout (dynamic): tile u16 [V][NCP] | tot f64 [NC] | keep u32 [NBW] | (SCORED) scores f32 [V][NC + 4]
+// SCORED: the selections are driven by the score matrix a.Sc instead of |w| (Section 3, steps 2-3 on
+// any importance score, e.g. RIA, Eq. 1): column norms are the fp64 sums of the scores added in row
+// order (their value can depend on the order, so it is fixed), step 3 compares the scores; the kept
+// values are W's.  The plain instantiation is the kernel of the hot path, unchanged.
+template <bool SCORED>
 __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int V = a.V, M = a.M;
@@ -62,6 +82,8 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   unsigned short* tile = (unsigned short*)smem;
   double* tot = (double*)(smem + (size_t)V * NCP * 2);
   unsigned* keep = (unsigned*)(tot + NC);
+  float* stile = (float*)(keep + NBW);
+  const int NCS = NC + 4;                           // score tile pitch in floats (16-byte rows)
   const int tid = threadIdx.x;
   const int chunks = NC / 8;
 
@@ -93,16 +115,42 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         if (vv < V) {
           *(uint4*)(tile + (size_t)vv * NCP + ch * 8) = w[u];
           const unsigned d[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+          if constexpr (!SCORED) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += fp16_abs_f64(d[e] & 0xFFFFu);
-            acc[2 * e + 1] += fp16_abs_f64(d[e] >> 16);
+            for (int e = 0; e < 4; ++e) {
+              acc[2 * e] += fp16_abs_f64(d[e] & 0xFFFFu);
+              acc[2 * e + 1] += fp16_abs_f64(d[e] >> 16);
+            }
           }
         }
       }
     }
+    if constexpr (!SCORED) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) unsafeAtomicAdd(tot + ch * 8 + e, acc[e]);
+      for (int e = 0; e < 8; ++e) unsafeAtomicAdd(tot + ch * 8 + e, acc[e]);
+    }
+  }
+  if constexpr (SCORED) {
+    // score tile -> LDS with 16-byte accesses (zero where the matrix is padded), then one thread per
+    // column adds its V scores in row order
+    const int chunks4 = NC / 4;
+    const int G4 = 256 / chunks4;
+    if (tid < chunks4 * G4) {
+      const int g = tid / chunks4, ch = tid - g * chunks4;
+      const int64_t col = c0 + ch * 4;
+      for (int v = g; v < V; v += G4) {
+        const int64_t row = r * V + v;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < a.out && col < a.in) s = *(const float4*)(a.Sc + row * a.lds_s + col);
+        *(float4*)(stile + (size_t)v * NCS + ch * 4) = s;
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < NC; c += 256) {
+      double acc = 0.0;
+      for (int v = 0; v < V; ++v) acc += (double)stile[(size_t)v * NCS + c];
+      tot[c] = acc;
+    }
   }
   __syncthreads();
   // phase 1: per block keep the 4 columns of largest L1 norm (ties to the lower index), ascending:
@@ -146,7 +194,16 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
         const unsigned short* tb = trow + g * M;
         const unsigned w0 = tb[kp[g] & 255u], w1 = tb[(kp[g] >> 8) & 255u], w2 = tb[(kp[g] >> 16) & 255u],
                        w3 = tb[kp[g] >> 24];
-        const unsigned nib = top2_of_4_f(w0, w1, w2, w3, q[g]);
+        unsigned nib;
+        if constexpr (SCORED) {
+          const float* sb = stile + (size_t)v * NCS + (blk0 + g) * M;
+          nib = top2_of_4_s(__float_as_uint(sb[kp[g] & 255u]) & 0x7FFFFFFFu, __float_as_uint(sb[(kp[g] >> 8) & 255u]) & 0x7FFFFFFFu,
+                            __float_as_uint(sb[(kp[g] >> 16) & 255u]) & 0x7FFFFFFFu, __float_as_uint(sb[kp[g] >> 24]) & 0x7FFFFFFFu);
+          const unsigned w4[4] = {w0, w1, w2, w3};
+          q[g] = w4[nib & 3] | (w4[nib >> 2] << 16);
+        } else {
+          nib = top2_of_4_f(w0, w1, w2, w3, q[g]);
+        }
         ix |= nib << (4 * g);
       }
       ixs[at] = (unsigned short)ix;
@@ -259,9 +316,9 @@ static int prune_fast_ksw(const Dims& d) {
   return k;
 }
 
-static size_t prune_fast_lds(int V, int M, int KSW) {
+static size_t prune_fast_lds(int V, int M, int KSW, bool scored = false) {
   const size_t NC = (size_t)KSW * 8 * M, NBW = (size_t)KSW * 8;
-  return (size_t)V * (NC + 8) * 2 + NC * 8 + NBW * 4;
+  return (size_t)V * (NC + 8) * 2 + NC * 8 + NBW * 4 + (scored ? (size_t)V * (NC + 4) * 4 : 0);
 }
 
 bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask) {
@@ -269,9 +326,42 @@ bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void
          d.S <= 65535;
 }
 
+// Score-driven variant: the same kernel with the score tile next to the weight tile in LDS
+bool prune_fast_scored_applicable(const void* W, int64_t ldw, const void* S, int64_t lds_s, const Dims& d) {
+  return prune_fast_applicable(W, ldw, d, nullptr) && lds_s % 4 == 0 && ((uintptr_t)S & 15) == 0 &&
+         prune_fast_lds(d.V, d.M, 1, true) <= 64 * 1024;
+}
+
+int launch_prune_fast_scored(const void* W, int64_t ldw, const void* S, int64_t lds_s, const Dims& d, void* values,
+                             void* meta, void* colidx, void* mask, void* packed, hipStream_t st) {
+  PruneFastArgs a{};
+  a.W = (const unsigned short*)W; a.ldw = ldw; a.out = d.out; a.in = d.in; a.V = d.V; a.M = d.M;
+  a.R = d.R; a.B = d.B; a.S = d.S;
+  a.Sc = (const float*)S; a.lds_s = lds_s;
+  int k = 8;
+  while (k > 1 && prune_fast_lds(d.V, d.M, k, true) > 64 * 1024) k >>= 1;     // two workgroups per CU at least
+  a.KSW = k;
+  const int chunks = a.KSW * d.M;
+  a.G = 256 / chunks < d.V ? 256 / chunks : d.V;
+  a.values = (unsigned short*)values; a.meta = (unsigned char*)meta; a.colidx = (unsigned char*)colidx;
+  a.mask = (unsigned char*)mask;
+  if (packed) {
+    const PackedLayout pl = packed_layout(d);
+    char* p = (char*)packed;
+    a.pa = (uint4*)(p + pl.pa_off); a.pidx = (unsigned short*)(p + pl.pidx_off); a.pcol = (unsigned*)(p + pl.pcol_off);
+  }
+  const size_t lds = prune_fast_lds(d.V, d.M, a.KSW, true);
+  if (int rc_lds = allow_big_lds((const void*)prune_pack_kernel<true>, "hipFuncSetAttribute(prune_pack scored)")) return rc_lds;
+  dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
+  hipLaunchKernelGGL(prune_pack_kernel<true>, grid, dim3(256), lds, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "prune_pack_kernel<scored>"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
 int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, void* meta, void* colidx,
                       void* mask, void* packed, hipStream_t st) {
-  PruneFastArgs a;
+  PruneFastArgs a{};
   a.W = (const unsigned short*)W; a.ldw = ldw; a.out = d.out; a.in = d.in; a.V = d.V; a.M = d.M;
   a.R = d.R; a.B = d.B; a.S = d.S;
   a.KSW = prune_fast_ksw(d);
@@ -286,11 +376,11 @@ int launch_prune_fast(const void* W, int64_t ldw, const Dims& d, void* values, v
     a.pa = (uint4*)(p + pl.pa_off); a.pidx = (unsigned short*)(p + pl.pidx_off); a.pcol = (unsigned*)(p + pl.pcol_off);
   }
   const size_t lds = prune_fast_lds(d.V, d.M, a.KSW);
-  if (int rc_lds = allow_big_lds((const void*)prune_pack_kernel, "hipFuncSetAttribute(prune_pack)")) return rc_lds;
+  if (int rc_lds = allow_big_lds((const void*)prune_pack_kernel<false>, "hipFuncSetAttribute(prune_pack)")) return rc_lds;
   // row blocks along x: workgroups that share a span of columns' cache lines with their
   // neighbours in y sit R apart in launch order
   dim3 grid((unsigned)d.R, (unsigned)((d.S + a.KSW - 1) / a.KSW));
-  hipLaunchKernelGGL(prune_pack_kernel, grid, dim3(256), lds, st, a);
+  hipLaunchKernelGGL(prune_pack_kernel<false>, grid, dim3(256), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "prune_pack_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

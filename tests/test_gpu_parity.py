@@ -182,6 +182,8 @@ SPLITK_CASES = [
     # out, in, T, V, M: few tokens, enough K steps (in / 8M) for the product to be split along K
     (1024, 4096, 16, 64, 5), (960, 2048, 1, 64, 8), (512, 3000, 40, 128, 6), (640, 5120, 130, 64, 16),
     (1000, 4104, 7, 64, 5),
+    # more than 256 tokens on matrices with few row groups: split while the grid would leave most CUs idle
+    (1024, 4096, 300, 64, 5), (2048, 8192, 700, 64, 8), (4096, 8000, 1000, 64, 5),
 ]
 
 

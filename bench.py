@@ -127,7 +127,8 @@ def L0_is_default(layers):
 
 def cpu_baseline(layers):
     """The oracle as it stands on the host cores: the whole path (prune + compress, decompress,
-    masked-dense fp64 product) on every layer of the step with a 256-token slice of X."""
+    masked-dense fp64 product) on every layer of the step with a 1024-token slice of X (sized for
+    10-30 s of host work)."""
     import numpy as np
     import synth_inputs as syn
     from oracle import vnm_oracle as orc
@@ -137,7 +138,7 @@ def cpu_baseline(layers):
     except Exception:
         threads = os.cpu_count() or 1
     dt, flops = 0.0, 0.0
-    Tp = min(256, layers[0].tokens)
+    Tp = min(1024, layers[0].tokens)
     for layer in layers:
         W, X = syn.layer_tensors(layer, tokens=Tp)
         t0 = time.perf_counter()

@@ -12,7 +12,8 @@
 // of 4 column blocks -- with 16 two-byte LDS reads at the offsets of the packed column table
 // (conflict-free: lanes differ in the row).  That is 16 LDS instructions per matrix instruction
 // pair, far below what the streaming rate needs; the transposing staged layout of the many-token
-// kernel would cost a second launch.
+// kernel would cost a second launch.  For at most 16 tokens a second kernel (further down) keeps the
+// whole slice of X in LDS and uses the registers for a deeper weight stream instead.
 #include "vnm_internal.h"
 
 namespace vnm {
@@ -35,6 +36,7 @@ struct SkinnyArgs {
   // split K: workgroup (r, z) walks phases [z * npz, min(nph, (z + 1) * npz)) and writes its fp32
   // partial product at Y + z * z_stride elements (a scratch then; summed by splitk_reduce)
   int npz; int64_t z_stride;
+  int nsz;                       // resident-X kernel: K steps per workgroup (split K as above, counted in steps)
   // fused epilogue (null = none): bias per weight row, destination channel per weight row
   const _Float16* bias; const int* perm_out;
 };
@@ -200,6 +202,173 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
   }
 }
 
+// Up to 16 tokens whose slice of X fits LDS as a whole (16 rows of the workgroup's K range: in <= ~4800
+// columns unsplit, more with split K): X is fetched once, up front, and then nothing is written to LDS
+// any more, so the K loop needs no barrier and no registers for X.  The registers go to the weight
+// stream instead: every wave keeps 8 to 10 A operands (steps wave, wave + 8, ...) requested ahead of the
+// one it multiplies -- twice the bytes in flight of the phased kernel above, which is what a stream
+// that is bound by memory round trips, not by bytes, needs.  All loads are unconditional (clamped to
+// the last step), so the compiler can wait for exactly the operand it uses next.
+constexpr int kSkNXR = 20;       // 16-byte pieces of X per thread, at most (16 rows of at most 9600 bytes)
+
+template <bool DUAL>
+__global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(const SkinnyArgs a) {
+  constexpr int AT = 2, TT = 16;
+  constexpr int kSkRing = 8;                         // more (10 fit without spilling) measured no faster
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t r = blockIdx.x;
+  const int M = a.M;
+  const int64_t S = a.S;
+  const int64_t s_lo = (int64_t)blockIdx.y * a.nsz;
+  const int64_t s_hi = s_lo + a.nsz < S ? s_lo + a.nsz : S;
+  const int ncol = a.nsz * 8 * M;                    // raw columns of a workgroup's K range
+  const int pitch = ncol * 2 + 4;                    // bytes per token row: odd number of dwords
+  const int64_t col0 = s_lo * 8 * M;
+
+  struct AOp { uint4 w[AT]; unsigned idx; uint4 pc, pc2; };
+  const int hB = lane >> 5;
+  auto load_a = [&](AOp& o, int64_t s) {
+    s = s < S ? s : S - 1;                           // beyond the range: a valid operand that is never used
+    const int64_t rs = r * S + s;
+#pragma unroll
+    for (int t = 0; t < AT; ++t) o.w[t] = a.pa[(rs * AT + t) * 64 + lane];
+    o.idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
+    if (DUAL) { o.pc = a.pcol[rs * 4 + hB * 2]; o.pc2 = a.pcol[rs * 4 + hB * 2 + 1]; }
+    else o.pc = a.pcol[rs * 2 + hB];
+  };
+  AOp ring[kSkRing];
+#pragma unroll
+  for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
+
+  // X slice -> LDS, [token][raw column]; piece i of a thread is (token, 16-byte chunk) number
+  // tid + 512 i in row-major order, fetched in two batches; rows beyond T and columns beyond `in`
+  // become zero
+  {
+    const int CH = ncol / 8;
+    int tok = tid / CH, ch = tid - tok * CH;
+    const int dtok = 512 / CH, dch = 512 - dtok * CH;
+    constexpr int HB = kSkNXR / 2;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      uint4 xw[HB];
+      int tok2 = tok, ch2 = ch;
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        const bool ok = tok2 < TT && tok2 < a.T && col0 + ch2 * 8 < a.in;
+        const unsigned short* src = ok ? a.X + tok2 * a.ldx + col0 + ch2 * 8 : a.X;
+        xw[i] = *(const uint4*)src;
+        ch2 += dch; tok2 += dtok;
+        if (ch2 >= CH) { ch2 -= CH; ++tok2; }
+      }
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        if (tok < TT) {
+          const bool ok = tok < a.T && col0 + ch * 8 < a.in;
+          const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);
+          unsigned* d = (unsigned*)(smem + (size_t)tok * pitch + ch * 16);
+          d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+        }
+        ch += dch; tok += dtok;
+        if (ch >= CH) { ch -= CH; ++tok; }
+      }
+    }
+  }
+  __syncthreads();
+
+  sk_f16 acc[AT];
+#pragma unroll
+  for (int t = 0; t < AT; ++t)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc[t][k] = 0.f;
+
+  const int tokl = lane & 15;                        // lanes 16..31 repeat tokens 0..15
+  auto compute = [&](const AOp& o, int64_t s) {
+    const unsigned char* row = smem + (size_t)tokl * pitch + (size_t)(s - s_lo) * 16 * M;
+    unsigned pc[2][4];
+    if (DUAL) {
+      pc[0][0] = o.pc.x; pc[1][0] = o.pc.y; pc[0][1] = o.pc.z; pc[1][1] = o.pc.w;
+      pc[0][2] = o.pc2.x; pc[1][2] = o.pc2.y; pc[0][3] = o.pc2.z; pc[1][3] = o.pc2.w;
+    } else {
+      pc[0][0] = o.pc.x; pc[0][1] = o.pc.y; pc[0][2] = o.pc.z; pc[0][3] = o.pc.w;
+    }
+    const int ix = (int)o.idx;
+#pragma unroll
+    for (int t = 0; t < (DUAL ? 2 : 1); ++t) {
+      sk_u8 bw;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        unsigned v[4];
+#pragma unroll
+        for (int kq = 0; kq < 4; ++kq) v[kq] = *(const unsigned short*)(row + 2 * ((pc[t][kq] >> (8 * m)) & 255u));
+        bw[2 * m] = v[0] | (v[1] << 16);
+        bw[2 * m + 1] = v[2] | (v[3] << 16);
+      }
+      const sk_h16 bv = __builtin_bit_cast(sk_h16, bw);
+      if (!DUAL || t == 0)
+        acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[0]), bv, acc[0], ix, 0, 0);
+      if (!DUAL || t == 1)
+        acc[1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[1]), bv, acc[1], ix, 0, 1);
+    }
+  };
+
+  for (int64_t sb = s_lo + wave; sb < s_hi; sb += kSkWaves * kSkRing) {
+#pragma unroll
+    for (int i = 0; i < kSkRing; ++i) {
+      const int64_t s = sb + kSkWaves * i;
+      if (s < s_hi) compute(ring[i], s);
+      load_a(ring[i], s + kSkWaves * kSkRing);
+    }
+  }
+  __syncthreads();                                   // every wave is done with X: the reduction reuses its LDS
+
+  constexpr int RW = AT * 32;
+  float* red = (float*)smem;
+  if ((lane & 31) < TT) {
+    float* mine = red + ((size_t)wave * TT + (lane & 31)) * (RW + 1);
+#pragma unroll
+    for (int t = 0; t < AT; ++t)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mine[t * 32 + 8 * (j >> 2) + 4 * hB + (j & 3)] = acc[t][j];
+  }
+  __syncthreads();
+  for (int e = tid; e < TT * RW; e += 64 * kSkWaves) {
+    const int tok = e / RW, rw = e - tok * RW;
+    const int64_t o = r * RW + rw;
+    if (tok < a.T && o < a.out) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kSkWaves; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
+      if (a.bias) sum += (float)a.bias[o];
+      const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
+      if (dst < 0 || dst >= a.out) continue;
+      if (a.y_fp32) ((float*)a.Y)[(int64_t)blockIdx.y * a.z_stride + tok * a.ldy + dst] = sum;
+      else ((_Float16*)a.Y)[tok * a.ldy + dst] = (_Float16)sum;
+    }
+  }
+}
+
+// LDS of the resident-X kernel for nsz K steps per workgroup; 0 if they do not fit
+static size_t skinny_resident_lds(int M, int64_t nsz) {
+  const size_t x = (size_t)16 * ((size_t)nsz * 16 * M + 4);
+  const size_t red = (size_t)kSkWaves * 16 * (2 * 32 + 1) * 4;
+  const size_t lds = x > red ? x : red;
+  // kSkNXR pieces per thread cover the slice: 16 rows x (nsz M) chunks <= 512 kSkNXR
+  if (lds > 150 * 1024 || (size_t)16 * nsz * M > (size_t)512 * kSkNXR) return 0;
+  return lds;
+}
+
+template <bool DUAL>
+static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
+  auto kern = spmm_skinny_resident_kernel<DUAL>;
+  if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
+  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS), dim3(64 * kSkWaves), lds, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
+  return VNM_OK;
+}
+
 int64_t skinny_max_tokens() { return 32; }
 
 template <bool DUAL, int TT>
@@ -233,6 +402,32 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
+  if (T <= 16) {
+    // resident-X kernel: K split over workgroups (with scratch) while they all still fit the 256 CUs at
+    // once, at least 8 steps each; taken if the workgroup's slice of X fits LDS
+    int64_t ks = 1;
+    if (scratch && R <= 128) {
+      ks = 256 / R;
+      if (ks > 16) ks = 16;
+      if (ks > d.S / 8) ks = d.S / 8;
+      if (ks < 1) ks = 1;
+      while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
+    }
+    const int64_t nsz = (d.S + ks - 1) / ks;
+    const int KSr = (int)((d.S + nsz - 1) / nsz);
+    // below 32 steps per workgroup (4 per wave) there is nothing to keep in flight: the phased kernel
+    const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz) : 0;
+    if (lds) {
+      a.nsz = (int)nsz; a.z_stride = 0;
+      if (KSr > 1) {
+        a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
+        a.bias = nullptr; a.perm_out = nullptr;                           // applied by the reduction
+      }
+      const int rc = dual ? launch_skinny_resident<true>(a, R, KSr, lds, st) : launch_skinny_resident<false>(a, R, KSr, lds, st);
+      if (rc != VNM_OK || KSr == 1) return rc;
+      return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
+    }
+  }
   // steps per phase: a multiple of the 8 waves, at most 32, with at most kSkNX pieces of X per thread
   // (TT * P * M <= 512 * kSkNX), which also keeps the two LDS buffers below 132 KiB
   int P = 512 * kSkNX / (TT * d.M) / 8 * 8;

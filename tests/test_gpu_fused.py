@@ -38,6 +38,8 @@ FUSED_CASES = [
     (192, 160, 130, 64, 5), (96, 200, 300, 32, 5), (256, 264, 77, 128, 6), (130, 96, 200, 64, 7),
     (64, 640, 257, 64, 16), (384, 384, 520, 64, 5), (512, 2048, 100, 64, 5), (1024, 1280, 40, 64, 8),
     (130, 96, 300, 64, 7), (2048, 512, 24, 64, 5),
+    # at most 16 tokens, X resident in LDS: epilogue in the kernel (unsplit) and in the reduction (split K)
+    (8256, 1320, 12, 64, 5), (4096, 5600, 16, 64, 5),
 ]
 WHICH = [("bias",), ("perm_in",), ("perm_out",), ("bias", "perm_in", "perm_out")]
 

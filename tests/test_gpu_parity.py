@@ -214,6 +214,38 @@ def test_spmm_few_tokens_split_k(out, inn, T, V, M, ydt):
     assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
 
 
+RESIDENT_X_CASES = [
+    # out, in, T, V, M: at most 16 tokens and at least 32 K steps (in / 8M) per workgroup -- the few-token kernel
+    # that keeps the workgroup's slice of X in LDS: unsplit (more than 128 row blocks), with two column tables
+    # (V = 32), with 128-row blocks, and with K split over 4 and over 16 workgroups
+    (8256, 2048, 16, 64, 5), (8256, 2080, 9, 32, 6), (8320, 4104, 13, 128, 8), (4096, 11008, 16, 64, 5),
+    (640, 20480, 1, 64, 5),
+]
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", RESIDENT_X_CASES)
+@pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
+def test_spmm_up_to_16_tokens_x_resident_in_lds(out, inn, T, V, M, ydt):
+    """The few-token kernel with X resident in LDS and a ring of weight operands in flight, against the
+    oracle; with integer-valued operands bit for bit against the general kernel."""
+    rng = np.random.default_rng(out + inn + T)
+    W = _rand_w(rng, out, inn, "normal")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=ydt, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
+    assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
+    Wi, Xi = syn.small_integer_case(out, inn, T, seed=T + M, lo=-2, hi=2)
+    ci = vnm.vnm_prune_compress(_dev(Wi), V, M, want_mask=True)
+    Ya = vnm.vnm_spmm(_dev(Xi), ci, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+    Yb = vnm.vnm_spmm(_dev(Xi), ci, out_dtype=torch.float32, path=vnm.PATH_GENERIC)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
+    Yi_ref = orc.matmul_ref(Xi, orc.masked_dense(Wi, ci.mask.cpu().numpy()))
+    assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
+
+
 def test_spmm_pad_columns_are_never_read():
     """in = 72 at M = 5 pads to 75: the pad columns must count as zero even when the memory right
     after each X row holds NaN."""

@@ -403,14 +403,16 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
   if (T <= 16) {
-    // resident-X kernel: K split over workgroups (with scratch) while they all still fit the 256 CUs at
-    // once, at least 8 steps each; taken if the workgroup's slice of X fits LDS
+    // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
+    // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
+    // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
+    // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
+    // in four against 18.1 us split in two)
     int64_t ks = 1;
-    if (scratch && R <= 128) {
+    if (scratch && R <= 128 && d.S > 128) {
       ks = 256 / R;
       if (ks > 16) ks = 16;
-      if (ks > d.S / 8) ks = d.S / 8;
-      if (ks < 1) ks = 1;
+      if (ks > d.S / 32) ks = d.S / 32;
       while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
     }
     const int64_t nsz = (d.S + ks - 1) / ks;

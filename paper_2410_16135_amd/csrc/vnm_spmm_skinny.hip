@@ -243,15 +243,16 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
   for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
 
   // X slice -> LDS, [token][raw column]; piece i of a thread is (token, 16-byte chunk) number
-  // tid + 512 i in row-major order, fetched in two batches; rows beyond T and columns beyond `in`
-  // become zero
+  // tid + 512 i in row-major order, fetched in one or two batches; rows beyond T and columns beyond
+  // `in` become zero
   {
     const int CH = ncol / 8;
     int tok = tid / CH, ch = tid - tok * CH;
     const int dtok = 512 / CH, dch = 512 - dtok * CH;
-    constexpr int HB = kSkNXR / 2;
+    constexpr int NB = DUAL ? 2 : 1;                 // one batch where the registers allow it
+    constexpr int HB = kSkNXR / NB;
 #pragma unroll 1
-    for (int half = 0; half < 2; ++half) {
+    for (int half = 0; half < NB; ++half) {
       uint4 xw[HB];
       int tok2 = tok, ch2 = ch;
 #pragma unroll

@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
 // one it multiplies -- twice the bytes in flight of the phased kernel above, which is what a stream
 // that is bound by memory round trips, not by bytes, needs.  All loads are unconditional (clamped to
 // the last step), so the compiler can wait for exactly the operand it uses next.
-constexpr int kSkNXR = 20;       // 16-byte pieces of X per thread, at most (16 rows of at most 9600 bytes)
+constexpr int kSkNXR = 18;       // 16-byte pieces of X per thread, at most (16 rows of at most 9216 bytes)
 
 template <bool DUAL>
 __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(const SkinnyArgs a) {
@@ -239,40 +239,43 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
     else o.pc = a.pcol[rs * 2 + hB];
   };
   AOp ring[kSkRing];
-#pragma unroll
-  for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
 
-  // X slice -> LDS, [token][raw column]; piece i of a thread is (token, 16-byte chunk) number
-  // tid + 512 i in row-major order, fetched in one or two batches; rows beyond T and columns beyond
-  // `in` become zero
+  // X slice -> LDS, [token][raw column], in 16-byte pieces.  One wave-wide load takes a block of 4 token
+  // rows x 16 chunks (256-byte runs of a row: whole cache lines; in LDS the four rows start an odd number
+  // of dwords apart, so the 64 lanes' stores fall into 64 different banks); block number wave + 8 i is
+  // (token group b & 3, chunk group b >> 2).  Rows beyond T and columns beyond `in` become zero.  The
+  // first ring of weight operands is requested right after X: loads return in order, so X (from L2) is
+  // not held up behind the weights (from HBM), and the weights travel while X is being parked in LDS.
   {
     const int CH = ncol / 8;
-    int tok = tid / CH, ch = tid - tok * CH;
-    const int dtok = 512 / CH, dch = 512 - dtok * CH;
+    const int c_lo = lane & 15, rsub = lane >> 4;
     constexpr int NB = DUAL ? 2 : 1;                 // one batch where the registers allow it
     constexpr int HB = kSkNXR / NB;
-#pragma unroll 1
+#pragma unroll
     for (int half = 0; half < NB; ++half) {
       uint4 xw[HB];
-      int tok2 = tok, ch2 = ch;
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const bool ok = tok2 < TT && tok2 < a.T && col0 + ch2 * 8 < a.in;
-        const unsigned short* src = ok ? a.X + tok2 * a.ldx + col0 + ch2 * 8 : a.X;
+        const int b = wave + kSkWaves * (half * HB + i);
+        const int tok = (b & 3) * 4 + rsub, ch = (b >> 2) * 16 + c_lo;
+        const bool ok = ch < CH && tok < a.T && col0 + ch * 8 < a.in;
+        const unsigned short* src = ok ? a.X + tok * a.ldx + col0 + ch * 8 : a.X;
         xw[i] = *(const uint4*)src;
-        ch2 += dch; tok2 += dtok;
-        if (ch2 >= CH) { ch2 -= CH; ++tok2; }
+      }
+      if (half == 0) {
+#pragma unroll
+        for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        if (tok < TT) {
+        const int b = wave + kSkWaves * (half * HB + i);
+        const int tok = (b & 3) * 4 + rsub, ch = (b >> 2) * 16 + c_lo;
+        if (ch < CH) {
           const bool ok = tok < a.T && col0 + ch * 8 < a.in;
           const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);
           unsigned* d = (unsigned*)(smem + (size_t)tok * pitch + ch * 16);
           d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
         }
-        ch += dch; tok += dtok;
-        if (ch >= CH) { ch -= CH; ++tok; }
       }
     }
   }
@@ -355,8 +358,8 @@ static size_t skinny_resident_lds(int M, int64_t nsz) {
   const size_t x = (size_t)16 * ((size_t)nsz * 16 * M + 4);
   const size_t red = (size_t)kSkWaves * 16 * (2 * 32 + 1) * 4;
   const size_t lds = x > red ? x : red;
-  // kSkNXR pieces per thread cover the slice: 16 rows x (nsz M) chunks <= 512 kSkNXR
-  if (lds > 150 * 1024 || (size_t)16 * nsz * M > (size_t)512 * kSkNXR) return 0;
+  // kSkNXR wave-wide loads per wave cover the slice: 4 token groups x ceil(nsz M / 16) chunk groups
+  if (lds > 150 * 1024 || 4 * (((size_t)nsz * M + 15) / 16) > (size_t)kSkWaves * kSkNXR) return 0;
   return lds;
 }
 

@@ -83,11 +83,15 @@ stage_x_kernel(const unsigned short* __restrict__ X, int64_t T, int64_t ldx, int
     }
     __syncthreads();
     if (k + 1 < n_sub && (sub + 1) * kStageKC < S) load(sub + 1);
-    // item = (column c, token octet tq)
+    // item = (column c, token octet tq): a wave takes 8 octets x 8 columns, so that its 2-byte reads of a
+    // tile whose rows are an odd number of dwords apart fall into 32 different banks (the two columns of
+    // a dword share an address) and its stores are whole 128-byte lines; combination number
+    // wave + 4 i picks the half of the octets and the group of 8 columns
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       if (i < NI) {
-        const int tq = tid & 15, c = (tid >> 4) + 16 * i;
+        const int comb = (tid >> 6) + 4 * i;
+        const int tq = (comb & 1) * 8 + (tid & 7), c = (comb >> 1) * 8 + ((tid >> 3) & 7);
         const int ks = kStageKC == 2 ? (c >= 8 * M ? 1 : 0) : c / (8 * M), cr = c - ks * 8 * M;
         if (s_begin + ks < S) {
           const unsigned char* src = smem + (size_t)(tq * 8) * pitch + c * 2;

@@ -305,10 +305,10 @@ def main():
     # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled by the calibration
     # copy); known only for the default workload
     default_wl = (args.workload == "llama2_7b" and L0_is_default(layers))
-    traffic = 346.9e6 if default_wl else None
+    traffic = 347.1e6 if default_wl else None
     # matrix-core and LDS counters of the same kernel from the same profile (rocprofv3 --pmc, SQ block)
-    counters = {"mfma_busy_percent": 42.5, "lds_active_percent_of_cu_busy": 47.7,
-                "lds_bank_conflict_percent_of_lds_active": 31.6, "hbm_side_tb_per_s": 2.97,
+    counters = {"mfma_busy_percent": 42.4, "lds_active_percent_of_cu_busy": 47.1,
+                "lds_bank_conflict_percent_of_lds_active": 31.6, "hbm_side_tb_per_s": 2.99,
                 "source": "profiles/bench_llama2_7b_64-2-5_T4096.md"} if default_wl else None
     dense_total = sum(dense_ms[L.name] for L in layers)
     L0 = layers[0]

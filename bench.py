@@ -148,7 +148,23 @@ def cpu_baseline(layers):
         dt += time.perf_counter() - t0
         flops += 2.0 * Tp * layer.out * layer.inn
     L0 = layers[0]
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s dense-equivalent", "cores": int(threads),
+    # the same on one thread, first layer only, 256 tokens (a few seconds)
+    single = None
+    try:
+        from threadpoolctl import threadpool_limits
+        T1 = min(256, L0.tokens)
+        W, X = syn.layer_tensors(L0, tokens=T1)
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            values, meta, colidx, mask = orc.compress(W, L0.V, L0.M)
+            Wd = orc.decompress(values, meta, colidx, L0.out, L0.inn, L0.V, L0.M)
+            Y = orc.matmul_ref(X, Wd)
+            dt1 = time.perf_counter() - t0
+        single = {"value": 2.0 * T1 * L0.out * L0.inn / dt1 / 1e12, "cores": 1, "seconds": dt1,
+                  "sample": f"layer {L0.name} only, {T1} of {L0.tokens} tokens"}
+    except Exception:
+        pass
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s dense-equivalent", "cores": int(threads), "single_core": single,
             "kind": "oracle", "seconds": dt,
             "sample": f"all {len(layers)} layers of the step at {L0.V}:2:{L0.M}, whole path (prune+compress, "
                       f"decompress, fp64 masked-dense product), {Tp} of {L0.tokens} tokens"

@@ -246,6 +246,35 @@ def test_spmm_up_to_16_tokens_x_resident_in_lds(out, inn, T, V, M, ydt):
     assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
 
 
+def _random_few_token_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        V = int(rng.choice([32, 64, 128])); M = int(rng.choice([4, 5, 6, 7, 8, 11, 16]))
+        S = int(rng.choice([32, 33, 57, 103, 129, 140, 276]))
+        inn = S * 8 * M - 8 * int(rng.integers(0, M))
+        budget = 6_000_000 // inn
+        out = int(rng.integers(1, budget + 1)) if rng.random() < 0.7 else int(min(budget, rng.integers(129, 140) * 64))
+        cases.append((max(out, 1), inn, int(rng.integers(1, 17)), V, M))
+    return cases
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", _random_few_token_cases(16, 2024))
+def test_random_few_token_shapes(out, inn, T, V, M):
+    """Seeded random shapes with at most 16 tokens and at least 32 K steps (ragged `in`, one to many
+    row blocks, all block heights): integer-valued operands, so the product is exact in any order."""
+    Wi, Xi = syn.small_integer_case(out, inn, T, seed=out + inn + T, lo=-2, hi=2)
+    c = vnm.vnm_prune_compress(_dev(Wi), V, M, want_mask=True)
+    Y_ref = orc.matmul_ref(Xi, orc.masked_dense(Wi, c.mask.cpu().numpy()))
+    for ydt in (torch.float32, torch.float16):
+        Y = vnm.vnm_spmm(_dev(Xi), c, out_dtype=ydt, path=vnm.PATH_SMFMAC)
+        torch.cuda.synchronize()
+        if ydt == torch.float32:
+            assert np.array_equal(Y.cpu().numpy().astype(np.float64), Y_ref)
+        else:
+            assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
+
+
 def test_spmm_pad_columns_are_never_read():
     """in = 72 at M = 5 pads to 75: the pad columns must count as zero even when the memory right
     after each X row holds NaN."""

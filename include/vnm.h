@@ -153,8 +153,8 @@ int vnm_pack(const void* values, const void* meta, const void* colidx,
  *            the K dimension is split over workgroups; contents are scratch, nothing persists
  * The matrix-core kernel needs V in {32, 64, 128}, M <= 16, in % 8 == 0, ldx % 8 == 0 and X 16-byte
  * aligned; otherwise (or when `packed` is NULL) AUTO uses the generic kernel, which needs no
- * workspace.  For T <= 32 the matrix-core path is a single kernel that reads X directly and uses no
- * workspace.  For larger T, when the matrix-core kernel applies but the workspace is missing or too
+ * workspace.  For T <= 32 the matrix-core path is a single kernel that reads X directly and needs no
+ * workspace (if one is given, its scratch part may hold split-K partial products).  For larger T, when the matrix-core kernel applies but the workspace is missing or too
  * small the call fails with VNM_ERR_WORKSPACE instead of silently taking the slow kernel.
  * T == 0 is a successful no-op (X and Y may then be NULL).
  */

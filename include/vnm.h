@@ -213,14 +213,18 @@ int vnm_fold_permutations(const void* perm_out_prev, const void* perm_in_next, i
  * activations to several layers (the q/k/v projections or the gate/up projections of a block share
  * their input): re-lay X once, multiply many times.  Same arguments and errors as vnm_spmm;
  * `staged` (vnm_stage_x_bytes(T, in, M) bytes, 256-byte aligned) holds the re-laid activations and
- * depends only on T, in and M, not on the layer's weights.  `scratch` (vnm_spmm_scratch_bytes(T, out)
+ * depends only on T, in and M, not on the layer's weights; vnm_spmm_staged takes its size too and
+ * fails with VNM_ERR_WORKSPACE if it is below vnm_stage_x_bytes(T, in, M): that size includes three
+ * images of slack behind the last token tile, which the product kernel's look-ahead copies read (and
+ * never use), so a buffer sized for the tiles alone would be read out of bounds.
+ * `scratch` (vnm_spmm_scratch_bytes(T, out)
  * bytes, 256-byte aligned, or NULL) is the optional split-K scratch: without it, or with less than
  * asked for, the product is still correct, only slower for small T.  vnm_spmm_staged fails with
  * VNM_ERR_UNSUPPORTED where vnm_spmm would have used the generic kernel.
  */
 int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, int M,
                 void* staged, int64_t staged_bytes, void* stream);
-int vnm_spmm_staged(const void* staged, int64_t T, const void* packed,
+int vnm_spmm_staged(const void* staged, int64_t staged_bytes, int64_t T, const void* packed,
                     int64_t out, int64_t in, int V, int N, int M,
                     void* Y, int64_t ldy, int y_dtype,
                     void* scratch, int64_t scratch_bytes, void* stream);
@@ -304,6 +308,9 @@ const char* vnm_status_string(int status);
 /* Text of the last HIP error seen by the calling thread ("" if none). */
 const char* vnm_last_hip_error(void);
 int vnm_format_version(void);
+/* Hex SHA-256 of the sources and compiler flags this library was built from; the Python binding
+ * compares it with the sources in the tree and rebuilds a stale library before using it. */
+const char* vnm_source_hash(void);
 
 #ifdef __cplusplus
 }

@@ -25,20 +25,30 @@ class VnmSizes(ctypes.Structure):
 
 
 def lib_path() -> str:
-    """In-tree library; VNM_LIB_PATH overrides it (developer aid for A/B-testing kernel builds)."""
-    return os.environ.get("VNM_LIB_PATH") or os.path.join(_PKG_DIR, "libvnm.so")
+    """The in-tree library."""
+    return os.path.join(_PKG_DIR, "libvnm.so")
 
 
 def load_library():
-    """Load libvnm.so; build it first only if it has never been built.  Raises if neither works."""
+    """Load libvnm.so.  The library carries a hash of the sources it was built from; when it is
+    missing, or the sources have changed since, it is rebuilt first (hipcc needed), so results never
+    come from kernels that are no longer in the tree.  Raises if neither works."""
     global _LIB
     if _LIB is not None:
         return _LIB
+    from .build import build_library, built_hash, source_hash
     path = lib_path()
-    if not os.path.exists(path):
-        from .build import build_library
+    want = source_hash()
+    if built_hash(path) != want:
+        import sys
+        print("libvnm.so is missing or older than its sources: rebuilding", file=sys.stderr, flush=True)
         build_library()
+        if built_hash(path) != want:
+            raise VnmError(-1, "libvnm.so does not match its sources even after a rebuild")
     lib = ctypes.CDLL(path)
+    lib.vnm_source_hash.restype = ctypes.c_char_p
+    if lib.vnm_source_hash().decode() != want:
+        raise VnmError(-1, "the loaded libvnm.so reports a different source hash than its file")
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.vnm_query_sizes.argtypes = [i64, i64, ci, ci, ci, ctypes.POINTER(VnmSizes)]
     lib.vnm_prune_compress.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp, i64, vp]
@@ -66,7 +76,7 @@ def load_library():
     lib.vnm_fold_permutations.restype = ci
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]
     lib.vnm_stage_x.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
-    lib.vnm_spmm_staged.argtypes = [vp, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, i64, vp]
+    lib.vnm_spmm_staged.argtypes = [vp, i64, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, i64, vp]
     lib.vnm_stage_x.restype = ci
     lib.vnm_spmm_staged.restype = ci
     lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
@@ -412,7 +422,7 @@ def vnm_spmm_staged(staged, T: int, c: Compressed, N: int = 2, out_dtype=None, Y
         nb = vnm_spmm_scratch_bytes(T, c.out)
         if nb > 0:
             scratch = _workspace((staged.device, "splitk"), nb)
-    _check(load_library().vnm_spmm_staged(_ptr(staged), T, _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y),
+    _check(load_library().vnm_spmm_staged(_ptr(staged), staged.numel(), T, _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y),
                                           Y.stride(0) if T > 0 else c.out, y_dtype, _ptr(scratch),
                                           scratch.numel() if scratch is not None else 0, _stream(staged)),
            "vnm_spmm_staged")

@@ -262,7 +262,7 @@ extern "C" int vnm_stage_x(const void* X, int64_t T, int64_t ldx, int64_t in, in
   return launch_stage_x(X, T, ldx, d, nullptr, staged, (hipStream_t)stream);
 }
 
-extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed, int64_t out,
+extern "C" int vnm_spmm_staged(const void* staged, int64_t staged_bytes_given, int64_t T, const void* packed, int64_t out,
                                int64_t in, int V, int N, int M, void* Y, int64_t ldy, int y_dtype,
                                void* scratch, int64_t scratch_bytes, void* stream) {
   if (T != 0 && (!staged || !packed || !Y)) return VNM_ERR_NULL;
@@ -276,6 +276,8 @@ extern "C" int vnm_spmm_staged(const void* staged, int64_t T, const void* packed
   if (scratch_bytes < 0) return VNM_ERR_WORKSPACE;
   if (scratch && ((uintptr_t)scratch & 255)) return VNM_ERR_ALIGN;
   if (T == 0) return VNM_OK;
+  // the look-ahead copies of the product kernel read up to three images past the last tile
+  if (staged_bytes_given < staged_bytes(T, make_dims(out, in, V, M))) return VNM_ERR_WORKSPACE;
   return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype, scratch,
                             scratch ? scratch_bytes : 0, Fused{}, (hipStream_t)stream);
 }

@@ -56,6 +56,17 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 //     set2 v[244:247] v[248:251] v252 v253
 //   s[80:81] A values ptr, s[82:83] index ptr, s[84:85] column table ptr, s[86:87] image ptr,
 //   s[88:89] copy source
+// The accumulators leave the loop in registers that the compiled epilogue reads with ordinary
+// vector instructions.  The compiler cannot see the matrix instructions inside the assembly block,
+// so it inserts none of the wait states the hardware requires between a matrix-core write of a
+// register and a vector-ALU read of it (up to 18 for a 16-pass instruction): the block owns that
+// hazard and ends with 24 idle states of its own, whatever else stands between the last
+// v_smfmac and the exit.
+// Validated with the HIP compiler of ROCm 7.2.0 (HIP 7.2.26015, AMD clang 22.0.0git roc-7.2.0); the loops name physical registers
+// v178-v253 and s80-s89 and declare them clobbered, which needs the compiler to keep its own live
+// values below them: a build that fails with "register allocation" errors here means a newer
+// compiler needs more registers around the block.
+#define VNM_ASM_MFMA_DRAIN "s_nop 15\n s_nop 7\n"
 #define VNM_ASM_COPY(K4096)                                   \
   "s_add_u32 %[tci], %[woff], " #K4096 "\n"                   \
   "s_min_u32 %[tci], %[tci], %[clamp]\n"                      \
@@ -193,6 +204,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
       "9:\n"                                                                                      \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
       "s_barrier\n"                                                                               \
+      VNM_ASM_MFMA_DRAIN                                                                          \
       : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
         [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
         [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                    \
@@ -314,6 +326,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
       "9:\n"                                                                                      \
       "s_waitcnt vmcnt(0) lgkmcnt(0)\n"                                                           \
       "s_barrier\n"                                                                               \
+      VNM_ASM_MFMA_DRAIN                                                                          \
       : [a00] "+v"(acc[0][0]), [a01] "+v"(acc[0][1]), [a02] "+v"(acc[0][2]), [a03] "+v"(acc[0][3]), \
         [a10] "+v"(acc[1][0]), [a11] "+v"(acc[1][1]), [a12] "+v"(acc[1][2]), [a13] "+v"(acc[1][3]), \
         [rd] "+&s"(l_rd), [wr] "+&s"(l_wr), [n] "+&s"(l_n), [tci] "=&s"(l_tci)                    \

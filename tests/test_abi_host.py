@@ -87,10 +87,17 @@ def test_argument_errors(lib):
     assert lib.vnm_stage_x(good, 4, 100, 128, 5, a256, 1 << 30, None) == 2          # ldx < in
     assert lib.vnm_stage_x(good, 4, 128, 128, 17, a256, 1 << 30, None) == 3         # M beyond the matrix-core range
     assert lib.vnm_stage_x(good, 4, 128, 128, 5, a256, 16, None) == 5
-    assert lib.vnm_spmm_staged(a256, 4, None, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 1
-    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 16, 2, 8, good, 128, 0, None, 0, None) == 3
-    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, P(0x1008), 1 << 20, None) == 4   # scratch misaligned
-    assert lib.vnm_spmm_staged(a256, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, a256, -1, None) == 5
+    assert lib.vnm_spmm_staged(a256, 1 << 30, 4, None, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 1
+    assert lib.vnm_spmm_staged(a256, 1 << 30, 4, a256, 128, 128, 16, 2, 8, good, 128, 0, None, 0, None) == 3
+    assert lib.vnm_spmm_staged(a256, 1 << 30, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, P(0x1008), 1 << 20, None) == 4   # scratch misaligned
+    assert lib.vnm_spmm_staged(a256, 1 << 30, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, a256, -1, None) == 5
+    # a staged buffer sized for the token tiles alone lacks the three images of slack the product
+    # kernel's look-ahead reads: refused on the host (one tile of 128 x 128 at M = 8: 2 images of 20 KiB)
+    need = ctypes.c_int64(-1)
+    assert lib.vnm_stage_x_bytes(4, 128, 8, ctypes.byref(need)) == 0 and need.value == (2 + 3) * 20480
+    assert lib.vnm_spmm_staged(a256, 2 * 20480, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 5
+    assert lib.vnm_spmm_staged(a256, need.value - 1, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 5
+    assert lib.vnm_spmm_staged(a256, 0, 0, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 0      # T == 0: no-op
     # sizes: staged activations alone, split-K scratch (small token counts only), and their sum
     sb, kb = ctypes.c_int64(-1), ctypes.c_int64(-1)
     assert lib.vnm_stage_x_bytes(4096, 4096, 5, ctypes.byref(sb)) == 0 and sb.value == (32 * 103 + 3) * 13312

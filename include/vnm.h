@@ -165,6 +165,27 @@ int vnm_spmm(const void* X, int64_t T, int64_t ldx,
              void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * vnm_spmm for callers that cannot hand over or allocate a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * vnm_spmm without `workspace`: the re-laid activations and the split-K partial products go to a
+ * device array of VNM_NOALLOC_SCRATCH_BYTES that is part of the library image (every GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing, on the
+ * host side of HIP or the device.  A shape whose staged activations (vnm_stage_x_bytes(T, in, M),
+ * rounded up to 256) exceed the array fails with VNM_ERR_WORKSPACE and vnm_last_hip_error() says how
+ * much was needed; what the activations leave free serves as split-K scratch (less of it may mean a
+ * different split and so a different, equally valid, rounding than vnm_spmm with a full workspace).
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different
+ * streams or threads) race; calls on one stream are ordered and safe.  Nothing in the array has to
+ * start at zero: every byte a product reads is written by the same call first, apart from slack
+ * that is fetched and never used.
+ */
+#define VNM_NOALLOC_SCRATCH_BYTES (32ll << 20)
+int vnm_spmm_noalloc(const void* X, int64_t T, int64_t ldx,
+                     const void* values, const void* meta, const void* colidx, const void* packed,
+                     int64_t out, int64_t in, int V, int N, int M,
+                     void* Y, int64_t ldy, int y_dtype, int path, void* stream);
+
+/*
  * vnm_spmm with the steps that Section 4.2 says can be merged into the layer at inference (Eq. 6:
  * Y = P_o^T W_p P_i^T X, W_p = P_o W P_i the channel-permuted weight that was pruned) and the layer's
  * bias:

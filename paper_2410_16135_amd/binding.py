@@ -54,6 +54,8 @@ def load_library():
     lib.vnm_prune_compress.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.vnm_pack.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp]
     lib.vnm_spmm.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp, i64, vp]
+    lib.vnm_spmm_noalloc.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, ci, ci, vp]
+    lib.vnm_spmm_noalloc.restype = ci
     lib.vnm_spmm_fused.argtypes = [vp, i64, i64, vp, vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, i64, ci, ci,
                                    vp, i64, vp]
     lib.vnm_spmm_fused.restype = ci
@@ -108,8 +110,9 @@ def _check(status: int, what: str):
     if status != 0:
         lib = load_library()
         msg = lib.vnm_status_string(status).decode()
-        if status == 6:
-            msg += " (" + lib.vnm_last_hip_error().decode() + ")"
+        detail = lib.vnm_last_hip_error().decode()
+        if status == 6 or (status == 5 and what == "vnm_spmm_noalloc" and detail):
+            msg += " (" + detail + ")"
         raise VnmError(status, f"{what}: {msg}")
 
 
@@ -256,6 +259,24 @@ def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO
         _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
         _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
         _ptr(ws), ws_bytes, _stream(X)), "vnm_spmm")
+    return Y
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def vnm_spmm_noalloc(X, c: Compressed, Y, N: int = 2, path: int = PATH_AUTO):
+    """vnm_spmm into a caller-supplied Y with the library's built-in scratch instead of a workspace:
+    the call allocates nothing (for callers that cannot: graph capture, serving loops)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    T = X.shape[0]
+    assert X.shape[1] == c.inn and Y.shape == (T, c.out) and Y.stride(1) == 1
+    y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    _check(load_library().vnm_spmm_noalloc(
+        _ptr(X), T, X.stride(0) if T > 0 else c.inn, _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
+        _ptr(c.packed), c.out, c.inn, c.V, N, c.M, _ptr(Y), Y.stride(0) if T > 0 else c.out, y_dtype, path,
+        _stream(X)), "vnm_spmm_noalloc")
     return Y
 
 

@@ -213,6 +213,52 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
                    workspace, workspace_bytes, stream);
 }
 
+// ---- vnm_spmm_noalloc: the workspace of vnm_spmm as a device array inside the library image.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it
+// yields (one per device, each GPU has its own copy) is what kernels and size checks use.
+static __device__ __align__(256) unsigned char scratch[VNM_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch(void** ptr_out) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, void*>> per_device;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_hip_error(e, "hipGetDevice"); return VNM_ERR_HIP; }
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& p : per_device)
+    if (p.first == dev) { *ptr_out = p.second; return VNM_OK; }
+  void* ptr = nullptr;
+  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !ptr) { set_hip_error(e, "hipGetSymbolAddress(scratch)"); return VNM_ERR_HIP; }
+  per_device.push_back({dev, ptr});
+  *ptr_out = ptr;
+  return VNM_OK;
+}
+
+extern "C" int vnm_spmm_noalloc(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                                const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N,
+                                int M, void* Y, int64_t ldy, int y_dtype, int path, void* stream) {
+  // size check first (host arithmetic only), so that an oversized request never touches the device
+  if (check_pattern(out, in, V, N, M) == VNM_OK && T > 0 && has_packed(V, M)) {
+    const int64_t need = (staged_bytes(T, make_dims(out, in, V, M)) + 255) / 256 * 256;
+    const bool staged_path = path != VNM_PATH_GENERIC && packed && X && ldx >= in &&
+                             spmm_smfmac_applicable(X, ldx, make_dims(out, in, V, M)) && T > skinny_max_tokens();
+    if (staged_path && need > (int64_t)VNM_NOALLOC_SCRATCH_BYTES) {
+      snprintf(g_hip_error, sizeof(g_hip_error),
+               "vnm_spmm_noalloc: %lld tokens x %lld input channels need %lld bytes of staged activations, the "
+               "built-in scratch holds %lld; use vnm_spmm with a workspace",
+               (long long)T, (long long)in, (long long)need, (long long)VNM_NOALLOC_SCRATCH_BYTES);
+      return VNM_ERR_WORKSPACE;
+    }
+  }
+  void* ws = nullptr;
+  if (T > 0) {
+    if (int rc = noalloc_scratch(&ws)) return rc;
+  }
+  return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path, ws,
+                   ws ? (int64_t)VNM_NOALLOC_SCRATCH_BYTES : 0, stream);
+}
+
 extern "C" int vnm_spmm_fused(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                               const void* colidx, const void* packed, int64_t out, int64_t in, int V,
                               int N, int M, const void* bias, const void* perm_in, const void* perm_out,

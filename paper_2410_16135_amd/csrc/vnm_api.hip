@@ -135,10 +135,12 @@ extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx
   return launch_pack(values, meta, colidx, make_dims(out, in, V, M), packed, (hipStream_t)stream);
 }
 
-static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
-                     const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
-                     const Fused& f, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
-                     int64_t workspace_bytes, void* stream) {
+// Host-side argument checks of vnm_spmm and its variants; nothing here touches the device.
+// Returns a vnm_status, or kProceed when there is work to enqueue.
+static constexpr int kProceed = -1;
+static int spmm_validate(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                         const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
+                         const Fused& f, const void* Y, int64_t ldy, int y_dtype, int path, int64_t workspace_bytes) {
   if (!values || !meta || !colidx) return VNM_ERR_NULL;
   if (T != 0 && (!X || !Y)) return VNM_ERR_NULL;                 // an empty batch may come with null X, Y
   int rc = check_pattern(out, in, V, N, M);
@@ -153,6 +155,17 @@ static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, 
   if (packed && ((uintptr_t)packed & 255)) return VNM_ERR_ALIGN;
   if (((uintptr_t)f.bias & 1) || ((uintptr_t)f.perm_in & 15) || ((uintptr_t)f.perm_out & 3)) return VNM_ERR_ALIGN;
   if (T == 0) return VNM_OK;
+  const Dims d = make_dims(out, in, V, M);
+  if (path == VNM_PATH_SMFMAC && !(packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d))) return VNM_ERR_UNSUPPORTED;
+  return kProceed;
+}
+
+static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+                     const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
+                     const Fused& f, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
+                     int64_t workspace_bytes, void* stream) {
+  int rc = spmm_validate(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, f, Y, ldy, y_dtype, path, workspace_bytes);
+  if (rc != kProceed) return rc;
   Dims d = make_dims(out, in, V, M);
   hipStream_t st = (hipStream_t)stream;
   const bool fast_ok = packed && has_packed(V, M) && spmm_smfmac_applicable(X, ldx, d);
@@ -238,11 +251,15 @@ static int noalloc_scratch(void** ptr_out) {
 extern "C" int vnm_spmm_noalloc(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                                 const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N,
                                 int M, void* Y, int64_t ldy, int y_dtype, int path, void* stream) {
-  // size check first (host arithmetic only), so that an oversized request never touches the device
-  if (check_pattern(out, in, V, N, M) == VNM_OK && T > 0 && has_packed(V, M)) {
-    const int64_t need = (staged_bytes(T, make_dims(out, in, V, M)) + 255) / 256 * 256;
-    const bool staged_path = path != VNM_PATH_GENERIC && packed && X && ldx >= in &&
-                             spmm_smfmac_applicable(X, ldx, make_dims(out, in, V, M)) && T > skinny_max_tokens();
+  // argument and size checks first (host arithmetic only): a bad or oversized request never
+  // touches the device
+  int rc = spmm_validate(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path, 0);
+  if (rc != kProceed) return rc;
+  if (has_packed(V, M)) {
+    const Dims d = make_dims(out, in, V, M);
+    const int64_t need = (staged_bytes(T, d) + 255) / 256 * 256;
+    const bool staged_path = path != VNM_PATH_GENERIC && packed && spmm_smfmac_applicable(X, ldx, d) &&
+                             T > skinny_max_tokens();
     if (staged_path && need > (int64_t)VNM_NOALLOC_SCRATCH_BYTES) {
       snprintf(g_hip_error, sizeof(g_hip_error),
                "vnm_spmm_noalloc: %lld tokens x %lld input channels need %lld bytes of staged activations, the "
@@ -252,11 +269,9 @@ extern "C" int vnm_spmm_noalloc(const void* X, int64_t T, int64_t ldx, const voi
     }
   }
   void* ws = nullptr;
-  if (T > 0) {
-    if (int rc = noalloc_scratch(&ws)) return rc;
-  }
+  if ((rc = noalloc_scratch(&ws)) != VNM_OK) return rc;
   return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path, ws,
-                   ws ? (int64_t)VNM_NOALLOC_SCRATCH_BYTES : 0, stream);
+                   (int64_t)VNM_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int vnm_spmm_fused(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,

@@ -98,6 +98,15 @@ def test_argument_errors(lib):
     assert lib.vnm_spmm_staged(a256, 2 * 20480, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 5
     assert lib.vnm_spmm_staged(a256, need.value - 1, 4, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 5
     assert lib.vnm_spmm_staged(a256, 0, 0, a256, 128, 128, 64, 2, 8, good, 128, 0, None, 0, None) == 0      # T == 0: no-op
+    # the entry point without a workspace: same argument errors, and a request beyond its built-in
+    # scratch is refused with a message, all before anything touches a device (none exists here)
+    assert lib.vnm_spmm_noalloc(None, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None) == 1
+    assert lib.vnm_spmm_noalloc(good, 4, 127, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None) == 2
+    assert lib.vnm_spmm_noalloc(good, 4, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 2, None) == 3
+    assert lib.vnm_spmm_noalloc(good, 0, 128, good, good, good, None, 128, 128, 64, 2, 8, good, 128, 0, 0, None) == 0
+    assert lib.vnm_spmm_noalloc(a256, 4200, 4096, good, good, good, a256, 64, 4096, 64, 2, 5, good, 64, 0, 0, None) == 5
+    lib.vnm_last_hip_error.restype = ctypes.c_char_p
+    assert b"built-in scratch" in lib.vnm_last_hip_error()
     # sizes: staged activations alone, split-K scratch (small token counts only), and their sum
     sb, kb = ctypes.c_int64(-1), ctypes.c_int64(-1)
     assert lib.vnm_stage_x_bytes(4096, 4096, 5, ctypes.byref(sb)) == 0 and sb.value == (32 * 103 + 3) * 13312

@@ -253,6 +253,23 @@ int vnm_spmm_staged(const void* staged, int64_t staged_bytes, int64_t T, const v
 int vnm_stage_x_bytes(int64_t T, int64_t in, int M, int64_t* bytes);
 int vnm_spmm_scratch_bytes(int64_t T, int64_t out, int64_t* bytes);
 
+/*
+ * Host only.  Which kernel vnm_spmm (VNM_PATH_AUTO, `packed` given, X aligned as the matrix-core
+ * kernels need it, no input permutation) runs for T tokens with a workspace of the given size:
+ *   VNM_KERNEL_GENERIC     scalar kernel (no matrix-core copy for this V, M, or in % 8 != 0)
+ *   VNM_KERNEL_FEW_TOKENS  T <= 32: one kernel, X token-major in LDS
+ *   VNM_KERNEL_RESIDENT    one kernel without a staging pass: the workgroup's slice of X is turned
+ *                          around into LDS by the kernel itself (short K at any T; any K up to 256
+ *                          tokens, K cut into parts that are summed inside the kernel)
+ *   VNM_KERNEL_STAGED      staging pass + streaming matrix-core kernel (vnm_stage_x + vnm_spmm_staged)
+ * For measurement and tests; results never depend on the choice beyond rounding.
+ */
+typedef enum vnm_kernel_choice {
+  VNM_KERNEL_GENERIC = 0, VNM_KERNEL_FEW_TOKENS = 1, VNM_KERNEL_RESIDENT = 2, VNM_KERNEL_STAGED = 3
+} vnm_kernel_choice;
+int vnm_spmm_kernel_choice(int64_t T, int64_t out, int64_t in, int V, int N, int M,
+                           int64_t workspace_bytes, int* choice);
+
 /* Host only.  Bytes of workspace vnm_spmm wants for T tokens of this layer: staged activations
  * (rounded up to 256) + split-K scratch (0 if the matrix-core kernel does not exist for this V, M). */
 int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M, int64_t* bytes);

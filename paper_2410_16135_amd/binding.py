@@ -81,6 +81,8 @@ def load_library():
     lib.vnm_spmm_staged.argtypes = [vp, i64, i64, vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, i64, vp]
     lib.vnm_stage_x.restype = ci
     lib.vnm_spmm_staged.restype = ci
+    lib.vnm_spmm_kernel_choice.argtypes = [i64, i64, i64, ci, ci, ci, i64, ctypes.POINTER(ci)]
+    lib.vnm_spmm_kernel_choice.restype = ci
     lib.vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ctypes.POINTER(i64)]
     lib.vnm_spmm_workspace_bytes.restype = ci
     lib.vnm_ria_scores.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp]
@@ -423,6 +425,17 @@ def vnm_stage_x(X, M: int, staged=None):
     _check(load_library().vnm_stage_x(_ptr(X), T, X.stride(0) if T > 0 else inn, inn, M, _ptr(staged),
                                       staged.numel(), _stream(X)), "vnm_stage_x")
     return staged
+
+
+KERNEL_GENERIC, KERNEL_FEW_TOKENS, KERNEL_RESIDENT, KERNEL_STAGED = 0, 1, 2, 3
+
+
+def vnm_spmm_kernel_choice(T: int, c: Compressed, workspace_bytes: int, N: int = 2) -> int:
+    """Which kernel vnm_spmm runs for T tokens of this layer with a workspace of that size."""
+    ch = ctypes.c_int(-1)
+    _check(load_library().vnm_spmm_kernel_choice(T, c.out, c.inn, c.V, N, c.M, workspace_bytes, ctypes.byref(ch)),
+           "vnm_spmm_kernel_choice")
+    return ch.value
 
 
 def vnm_spmm_scratch_bytes(T: int, out: int) -> int:

@@ -210,9 +210,13 @@ static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, 
         scratch_bytes = xp_off - sb;
       }
     }
+    void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
+    // a slice of X that fits LDS needs no staging pass: one kernel straight from X (short K, or few
+    // tokens with K cut into parts whose partial products go to the scratch)
+    if (!stage_perm && spmm_resident_applicable(T, d, scratch ? scratch_bytes : 0))
+      return launch_spmm_resident(Xk, T, ldk, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
     rc = launch_stage_x(Xk, T, ldk, d, stage_perm, workspace, st);
     if (rc) return rc;
-    void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
     return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
   }
   return launch_spmm_generic(X, T, ldx, values, meta, colidx, d, Y, ldy, y_dtype, f, st);
@@ -341,6 +345,22 @@ extern "C" int vnm_spmm_staged(const void* staged, int64_t staged_bytes_given, i
   if (staged_bytes_given < staged_bytes(T, make_dims(out, in, V, M))) return VNM_ERR_WORKSPACE;
   return launch_spmm_smfmac(staged, T, packed, make_dims(out, in, V, M), Y, ldy, y_dtype, scratch,
                             scratch ? scratch_bytes : 0, Fused{}, (hipStream_t)stream);
+}
+
+extern "C" int vnm_spmm_kernel_choice(int64_t T, int64_t out, int64_t in, int V, int N, int M,
+                                      int64_t workspace_bytes, int* choice) {
+  if (!choice) return VNM_ERR_NULL;
+  int rc = check_pattern(out, in, V, N, M);
+  if (rc) return rc;
+  if (T < 0 || workspace_bytes < 0) return VNM_ERR_SHAPE;
+  const Dims d = make_dims(out, in, V, M);
+  *choice = VNM_KERNEL_GENERIC;
+  if (!has_packed(V, M) || in % 8 != 0) return VNM_OK;
+  if (T <= skinny_max_tokens()) { *choice = VNM_KERNEL_FEW_TOKENS; return VNM_OK; }
+  const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
+  *choice = spmm_resident_applicable(T, d, workspace_bytes > sb ? workspace_bytes - sb : 0) ? VNM_KERNEL_RESIDENT
+                                                                                            : VNM_KERNEL_STAGED;
+  return VNM_OK;
 }
 
 extern "C" int vnm_spmm_workspace_bytes(int64_t T, int64_t out, int64_t in, int V, int N, int M,

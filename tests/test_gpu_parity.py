@@ -160,8 +160,8 @@ def test_spmm_edge_cases():
 
 
 def test_stage_once_multiply_many():
-    """vnm_stage_x + vnm_spmm_staged equal vnm_spmm bit for bit, and one staging serves several
-    layers that share their input (as q/k/v or gate/up do)."""
+    """vnm_stage_x + vnm_spmm_staged equal vnm_spmm (bit for bit where vnm_spmm runs the same two
+    kernels), and one staging serves several layers that share their input (as q/k/v or gate/up do)."""
     rng = np.random.default_rng(21)
     inn, T, V, M = 320, 300, 64, 5
     X = rng.standard_normal((T, inn)).astype(np.float16)
@@ -173,7 +173,10 @@ def test_stage_once_multiply_many():
         Y1 = vnm.vnm_spmm_staged(staged, T, c, out_dtype=torch.float32)
         Y2 = vnm.vnm_spmm(Xd, c, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
         torch.cuda.synchronize()
-        assert torch.equal(Y1, Y2)
+        if vnm.vnm_spmm_kernel_choice(T, c, vnm.vnm_spmm_workspace_bytes(T, c)) == vnm.KERNEL_STAGED:
+            assert torch.equal(Y1, Y2)                       # the same two kernels
+        else:                                                # vnm_spmm took the single-kernel path: same values up to rounding
+            assert orc.max_normalised_error(Y2.cpu().numpy(), Y1.cpu().numpy().astype(np.float64)) <= 1e-5
         Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
         assert orc.max_normalised_error(Y1.cpu().numpy(), Y_ref) <= TOL
 

@@ -259,8 +259,8 @@ int vnm_spmm_scratch_bytes(int64_t T, int64_t out, int64_t* bytes);
  *   VNM_KERNEL_GENERIC     scalar kernel (no matrix-core copy for this V, M, or in % 8 != 0)
  *   VNM_KERNEL_FEW_TOKENS  T <= 32: one kernel, X token-major in LDS
  *   VNM_KERNEL_RESIDENT    one kernel without a staging pass: the workgroup's slice of X is turned
- *                          around into LDS by the kernel itself (short K at any T; any K up to 256
- *                          tokens, K cut into parts that are summed inside the kernel)
+ *                          around into LDS by the kernel itself (a K range that fits LDS; or at most
+ *                          1024 output channels and at least 8192 tokens, K streaming through LDS)
  *   VNM_KERNEL_STAGED      staging pass + streaming matrix-core kernel (vnm_stage_x + vnm_spmm_staged)
  * For measurement and tests; results never depend on the choice beyond rounding.
  */

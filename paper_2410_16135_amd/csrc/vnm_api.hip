@@ -211,10 +211,10 @@ static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, 
       }
     }
     void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
-    // a slice of X that fits LDS needs no staging pass: one kernel straight from X (short K, or few
-    // tokens with K cut into parts whose partial products go to the scratch)
-    if (!stage_perm && spmm_resident_applicable(T, d, scratch ? scratch_bytes : 0))
-      return launch_spmm_resident(Xk, T, ldk, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
+    // a K range that fits LDS (or streams through it for few output channels) needs no staging pass:
+    // one kernel straight from X
+    if (!stage_perm && spmm_resident_applicable(T, d))
+      return launch_spmm_resident(Xk, T, ldk, packed, d, Y, ldy, y_dtype, f, st);
     rc = launch_stage_x(Xk, T, ldk, d, stage_perm, workspace, st);
     if (rc) return rc;
     return launch_spmm_smfmac(workspace, T, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
@@ -357,9 +357,7 @@ extern "C" int vnm_spmm_kernel_choice(int64_t T, int64_t out, int64_t in, int V,
   *choice = VNM_KERNEL_GENERIC;
   if (!has_packed(V, M) || in % 8 != 0) return VNM_OK;
   if (T <= skinny_max_tokens()) { *choice = VNM_KERNEL_FEW_TOKENS; return VNM_OK; }
-  const int64_t sb = (staged_bytes(T, d) + 255) / 256 * 256;
-  *choice = spmm_resident_applicable(T, d, workspace_bytes > sb ? workspace_bytes - sb : 0) ? VNM_KERNEL_RESIDENT
-                                                                                            : VNM_KERNEL_STAGED;
+  *choice = spmm_resident_applicable(T, d) ? VNM_KERNEL_RESIDENT : VNM_KERNEL_STAGED;
   return VNM_OK;
 }
 

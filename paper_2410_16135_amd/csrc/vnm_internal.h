@@ -120,15 +120,12 @@ int64_t skinny_max_tokens();
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
                        const Fused& f, hipStream_t st);
-// Single-kernel product without a staging pass for slices of X that fit LDS (vnm_spmm_resident.hip):
-// short K at any token count, any K up to resident_max_tokens_split() tokens (then `scratch` holds
-// partial products and arrival counters, resident_scratch_bytes of it).
-bool spmm_resident_applicable(int64_t T, const Dims& d, int64_t scratch_bytes);
-int64_t resident_scratch_bytes(int64_t T, const Dims& d);
-int64_t resident_max_tokens_split();
+// Single-kernel product without a staging pass (vnm_spmm_resident.hip): the workgroup's slice of X
+// is turned around into LDS by the kernel itself; for a K range that fits LDS, or few enough
+// output channels for K to stream through LDS in chunks.
+bool spmm_resident_applicable(int64_t T, const Dims& d);
 int launch_spmm_resident(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
-                         void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
-                         const Fused& f, hipStream_t st);
+                         void* Y, int64_t ldy, int y_dtype, const Fused& f, hipStream_t st);
 // Y = sum of KS fp32 partial products [KS][T][out] held in `part` (+ bias, output permutation)
 int launch_splitk_reduce(const void* part, int KS, int64_t T, int64_t out, void* Y, int64_t ldy,
                          int y_dtype, const Fused& f, hipStream_t st);

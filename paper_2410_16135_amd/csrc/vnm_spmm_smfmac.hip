@@ -674,9 +674,6 @@ int64_t splitk_scratch_bytes(int64_t T, int64_t out) {
   if (T <= 0 || T > kSplitKMaxTokens) return 0;
   int64_t b = 16 * T * out * 4;
   if (b > kSplitKMaxBytes) b = kSplitKMaxBytes;
-  // up to resident_max_tokens_split() tokens the single-kernel path keeps its arrival counters
-  // behind its (at most 16) partial products
-  if (T <= resident_max_tokens_split()) b += 64 * 1024;
   return (b + 255) / 256 * 256;
 }
 

@@ -1,6 +1,6 @@
-"""GPU parity of the single-kernel product that keeps its slice of X in LDS (no staging pass): row
-mode (short K, any token count) and K mode (up to 256 tokens, K cut into parts that the kernel sums
-itself), through vnm_spmm / vnm_spmm_fused, against the CPU oracle."""
+"""GPU parity of the single-kernel product that turns its slice of X around into LDS itself (no
+staging pass): whole K range in LDS (short K, any token count) and K streaming through LDS in chunks
+(few output channels, many tokens), through vnm_spmm / vnm_spmm_fused, against the CPU oracle."""
 
 import numpy as np
 import pytest
@@ -28,15 +28,19 @@ ROW_MODE = [
     (384, 384, 1000, 64, 5), (1152, 384, 700, 64, 5), (200, 768, 333, 64, 8), (130, 256, 257, 32, 6),
     (520, 400, 4100, 128, 7), (64, 640, 300, 64, 16), (1000, 96, 520, 32, 4),
 ]
-K_MODE = [
-    # out, in, T, V, M: 33 to 256 tokens; K in one part or several, 1 to 8 row blocks per workgroup
-    (4096, 4096, 64, 64, 5), (4096, 4096, 33, 64, 5), (1024, 4096, 130, 64, 5), (11008, 2048, 192, 64, 8),
-    (640, 5120, 256, 64, 16), (130, 11008, 100, 32, 5), (8320, 1040, 77, 128, 6), (64, 64, 40, 64, 4),
-    (200, 333 * 8, 65, 32, 7),
+CHUNKED = [
+    # out, in, T, V, M: at most 1024 output channels, at least 8192 tokens, a K range beyond LDS, M <= 8:
+    # one or two held row blocks per wave, ragged last chunk, ragged token tile, both table layouts
+    (384, 1536, 8200, 64, 5), (768, 3072, 8193, 64, 8), (1000, 2048, 9000, 32, 6), (200, 4096, 8300, 128, 7),
+    (520, 1000, 8256, 64, 4),
+]
+SHORT_T = [
+    # 33 to 256 tokens with short K: still the whole-K form (several row parts fill the chip)
+    (4096, 640, 64, 64, 5), (11008, 384, 192, 64, 8), (64, 64, 40, 64, 4), (8320, 512, 77, 128, 6),
 ]
 
 
-@pytest.mark.parametrize("out,inn,T,V,M", ROW_MODE + K_MODE)
+@pytest.mark.parametrize("out,inn,T,V,M", ROW_MODE + CHUNKED + SHORT_T)
 @pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
 def test_resident_kernel_matches_oracle(out, inn, T, V, M, ydt):
     rng = np.random.default_rng(out + 3 * inn + 7 * T + V + M)
@@ -51,8 +55,8 @@ def test_resident_kernel_matches_oracle(out, inn, T, V, M, ydt):
     assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
 
 
-@pytest.mark.parametrize("out,inn,T,V,M", [(384, 384, 300, 64, 5), (130, 256, 600, 32, 6), (1024, 4096, 130, 64, 5),
-                                         (4096, 4096, 64, 64, 5), (130, 11008, 100, 32, 5), (192, 2048, 200, 128, 8)])
+@pytest.mark.parametrize("out,inn,T,V,M", [(384, 384, 300, 64, 5), (130, 256, 600, 32, 6), (384, 1536, 8200, 64, 5),
+                                         (1000, 2048, 8200, 32, 6), (4096, 640, 64, 64, 5), (192, 512, 200, 128, 8)])
 def test_resident_kernel_small_integers_exact(out, inn, T, V, M):
     """Integer-valued operands: every partial sum is exact, so the result equals the oracle exactly
     whatever the split of K over waves and workgroups -- a zero-tolerance check of the indexing."""
@@ -65,39 +69,11 @@ def test_resident_kernel_small_integers_exact(out, inn, T, V, M):
     assert np.array_equal(Y.cpu().numpy().astype(np.float64), Y_ref)
 
 
-def test_resident_kernel_is_deterministic_and_scratch_needs_no_clearing():
-    """K parts are summed in a fixed order by whichever workgroup arrives last, so repeated calls give
-    the same bits; the arrival slots are told apart by a per-call tag, so calls of different shapes may
-    reuse one workspace in any order, and a workspace full of ones (or of an old call's slots) works."""
-    rng = np.random.default_rng(5)
-    shapes = [(1024, 4096, 130, 64, 5), (640, 5120, 256, 64, 16), (2048, 4096, 64, 64, 5)]
-    cases = []
-    for (out, inn, T, V, M) in shapes:
-        W = (rng.standard_normal((out, inn)) * 0.02).astype(np.float16)
-        X = rng.standard_normal((T, inn)).astype(np.float16)
-        c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
-        assert _choice(T, c) == vnm.KERNEL_RESIDENT
-        cases.append((_dev(X), c, orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))))
-    nb = max(vnm.vnm_spmm_workspace_bytes(X.shape[0], c) for (X, c, _) in cases)
-    ws = torch.full((nb,), 0xFF, dtype=torch.uint8, device=DEV)
-    first = {}
-    for rep in range(6):
-        for i in (0, 1, 2, 1, 0):
-            X, c, Y_ref = cases[i]
-            Y = vnm.vnm_spmm(X, c, out_dtype=torch.float32, path=vnm.PATH_SMFMAC, workspace=ws)
-            torch.cuda.synchronize()
-            if i not in first:
-                first[i] = Y.clone()
-                assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
-            else:
-                assert torch.equal(Y, first[i])
-
-
 def test_resident_kernel_strided_unaligned_and_fused():
     """Leading dimensions above the widths, a Y that rules out vector stores, pad columns behind X
-    that hold NaN, and the fused epilogue (bias, output permutation) in both modes."""
+    that hold NaN, and the fused epilogue (bias, output permutation) in both forms."""
     rng = np.random.default_rng(6)
-    for (out, inn, T, V, M) in [(200, 384, 300, 64, 5), (200, 4096, 70, 64, 5)]:
+    for (out, inn, T, V, M) in [(200, 384, 300, 64, 5), (200, 2048, 8200, 64, 5)]:
         W = (rng.standard_normal((out, inn)) * 0.02).astype(np.float16)
         Xfull = np.full((T, inn + 24), np.nan, dtype=np.float16)
         Xfull[:, :inn] = rng.standard_normal((T, inn)).astype(np.float16)

@@ -44,6 +44,11 @@ def parse():
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm-only", action="store_true", help="time vnm_spmm alone (profiling aid)")
+    ap.add_argument("--sclk", action="store_true",
+                    help="also report the shader clock (rocm-smi) while the sparse product and the dense GEMM loop")
+    ap.add_argument("--no-dense-search", action="store_true",
+                    help="do not run the hipBLASLt algorithm search (a child process): the dense baseline is then "
+                         "torch.matmul alone and marked untuned; for runs under a profiler")
     ap.add_argument("--hot-path-only", action="store_true",
                     help="skip the sections after the timed region that run other kernels or other shapes "
                          "(RIA, fused layer, permutation search, few tokens): per-kernel profiler averages "
@@ -173,9 +178,9 @@ def dense_baseline_searched(layers, iters, warmup):
 
 
 def profile_counters():
-    """Counter figures of the dominant kernel from the committed rocprofv3 summary, with the hash of
-    the kernel sources they were taken at; `stale` says whether csrc/ has changed since."""
-    from paper_2410_16135_amd.build import source_hash
+    """Counter figures of the dominant kernel from the committed rocprofv3 summary.  The file names the
+    kernel sources it was measured on and their hash; `stale` says whether they have changed since."""
+    import hashlib
     try:
         kv = {}
         with open(COUNTERS_FILE) as f:
@@ -184,17 +189,65 @@ def profile_counters():
                 if "=" in line:
                     k, v = line.split("=", 1)
                     kv[k.strip()] = v.strip()
+        h = hashlib.sha256()
+        for rel in kv.get("sources", "").split():
+            h.update(rel.encode() + b"\0")
+            with open(os.path.join(ROOT, rel), "rb") as f:
+                h.update(f.read())
+            h.update(b"\0")
     except OSError:
         return None
     num = {}
     for k, v in kv.items():
+        if k in ("sources", "sources_hash", "commit"):
+            continue
         try:
             num[k] = float(v)
         except ValueError:
             num[k] = v
-    num["stale"] = kv.get("source_hash") != source_hash()
+    num["stale"] = kv.get("sources_hash") != h.hexdigest()
     num["file"] = os.path.relpath(COUNTERS_FILE, ROOT)
+    num["measured_at_commit"] = kv.get("commit", "")
     return num
+
+
+def clock_probe(run_sparse, run_dense, seconds=3.0):
+    """Shader clock while the sparse product and the dense GEMM run back to back for a few seconds each,
+    read from rocm-smi by a second thread (median of the samples taken inside each loop)."""
+    import subprocess
+    import threading
+    import torch
+    samples, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=10)
+                d = json.loads(r.stdout)
+                card = d[sorted(d.keys())[0]]
+                mhz = [v for k, v in card.items() if "sclk clock speed" in k]
+                if mhz:
+                    samples.append((time.time(), float(mhz[0].strip("()Mhz"))))
+            except Exception:                                       # noqa: BLE001 -- a missing sample is not an error
+                pass
+            time.sleep(0.15)
+    th = threading.Thread(target=poll, daemon=True)
+    th.start()
+    out = {}
+    for name, f in (("spmm", run_sparse), ("dense", run_dense)):
+        time.sleep(0.7)
+        t0 = time.time()
+        while time.time() - t0 < seconds:
+            for _ in range(50):
+                f()
+            torch.cuda.synchronize()
+        t1 = time.time()
+        inside = sorted(m for (t, m) in samples if t0 + 0.8 < t < t1)
+        out[name + "_sclk_mhz"] = inside[len(inside) // 2] if inside else None
+    stop.set()
+    th.join(timeout=15)
+    out["note"] = ("median of rocm-smi samples while each product loops for %.0f s; the published peaks are quoted at 2400 MHz" % seconds)
+    return out
 
 
 def block_groups(workload, layers):
@@ -438,7 +491,7 @@ def main():
     for (L, e0, e1) in evs:
         torch_ms[L.name].append(e0.elapsed_time(e1))
     torch_ms = {k: med(v) for k, v in torch_ms.items()}
-    searched, dense_desc = dense_baseline_searched(layers, n_it, n_warm)
+    searched, dense_desc = (None, "search switched off") if args.no_dense_search else dense_baseline_searched(layers, n_it, n_warm)
     if searched is not None:
         dense_ms = {L.name: min(searched[L.name]["median_ms"], torch_ms[L.name]) for L in layers}
         dense_desc += "; the faster of this and torch.matmul is taken per layer"
@@ -646,6 +699,15 @@ def main():
             "spmm_16_tokens_ms": t_16, "dense_16_tokens_ms": t_16d,
             "note": "HIP-event means including launch gaps; bytes counted: RIA reads W twice and writes fp32 "
                     "scores; scored pruning reads W and the scores"}
+    if args.sclk:
+        Lq, Wq, Xq, cq, Yq, _ = state[0]
+        if is_staged[Lq.name]:
+            vnm.vnm_stage_x(Xq, Lq.M, staged=staged)
+            result["clocks"] = clock_probe(lambda: vnm.vnm_spmm_staged(staged, Lq.tokens, cq, Y=Yq),
+                                           lambda: torch.matmul(Xq, Wq.t(), out=Yq))
+        else:
+            result["clocks"] = clock_probe(lambda: vnm.vnm_spmm(Xq, cq, Y=Yq, workspace=staged),
+                                           lambda: torch.matmul(Xq, Wq.t(), out=Yq))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(layers)
     print(json.dumps(result))

@@ -12,6 +12,7 @@ static thread_local char g_hip_error[256] = "";
 void set_hip_error(hipError_t e, const char* where) {
   snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", where, hipGetErrorString(e));
 }
+void set_error_text(const char* text) { snprintf(g_hip_error, sizeof(g_hip_error), "%s", text); }
 
 int allow_big_lds(const void* kernel, const char* what) {
   static std::mutex mu;
@@ -30,7 +31,7 @@ int allow_big_lds(const void* kernel, const char* what) {
 
 using namespace vnm;
 
-static int check_pattern(int64_t out, int64_t in, int V, int N, int M) {
+int vnm::check_pattern(int64_t out, int64_t in, int V, int N, int M) {
   if (out <= 0 || in <= 0) return VNM_ERR_SHAPE;
   if (N != 2) return VNM_ERR_UNSUPPORTED;                       // Section 4.1: N is always 2
   if (M < 4 || M > 255) return VNM_ERR_UNSUPPORTED;             // colidx is a byte
@@ -137,8 +138,7 @@ extern "C" int vnm_pack(const void* values, const void* meta, const void* colidx
 
 // Host-side argument checks of vnm_spmm and its variants; nothing here touches the device.
 // Returns a vnm_status, or kProceed when there is work to enqueue.
-static constexpr int kProceed = -1;
-static int spmm_validate(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+int vnm::spmm_validate(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                          const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
                          const Fused& f, const void* Y, int64_t ldy, int y_dtype, int path, int64_t workspace_bytes) {
   if (!values || !meta || !colidx) return VNM_ERR_NULL;
@@ -160,7 +160,7 @@ static int spmm_validate(const void* X, int64_t T, int64_t ldx, const void* valu
   return kProceed;
 }
 
-static int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
+int vnm::spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
                      const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N, int M,
                      const Fused& f, void* Y, int64_t ldy, int y_dtype, int path, void* workspace,
                      int64_t workspace_bytes, void* stream) {
@@ -228,54 +228,6 @@ extern "C" int vnm_spmm(const void* X, int64_t T, int64_t ldx, const void* value
                         int64_t workspace_bytes, void* stream) {
   return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path,
                    workspace, workspace_bytes, stream);
-}
-
-// ---- vnm_spmm_noalloc: the workspace of vnm_spmm as a device array inside the library image.
-// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it
-// yields (one per device, each GPU has its own copy) is what kernels and size checks use.
-static __device__ __align__(256) unsigned char scratch[VNM_NOALLOC_SCRATCH_BYTES];
-
-static int noalloc_scratch(void** ptr_out) {
-  static std::mutex mu;
-  static std::vector<std::pair<int, void*>> per_device;
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) { set_hip_error(e, "hipGetDevice"); return VNM_ERR_HIP; }
-  std::lock_guard<std::mutex> lock(mu);
-  for (const auto& p : per_device)
-    if (p.first == dev) { *ptr_out = p.second; return VNM_OK; }
-  void* ptr = nullptr;
-  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
-  if (e != hipSuccess || !ptr) { set_hip_error(e, "hipGetSymbolAddress(scratch)"); return VNM_ERR_HIP; }
-  per_device.push_back({dev, ptr});
-  *ptr_out = ptr;
-  return VNM_OK;
-}
-
-extern "C" int vnm_spmm_noalloc(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,
-                                const void* colidx, const void* packed, int64_t out, int64_t in, int V, int N,
-                                int M, void* Y, int64_t ldy, int y_dtype, int path, void* stream) {
-  // argument and size checks first (host arithmetic only): a bad or oversized request never
-  // touches the device
-  int rc = spmm_validate(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path, 0);
-  if (rc != kProceed) return rc;
-  if (has_packed(V, M)) {
-    const Dims d = make_dims(out, in, V, M);
-    const int64_t need = (staged_bytes(T, d) + 255) / 256 * 256;
-    const bool staged_path = path != VNM_PATH_GENERIC && packed && spmm_smfmac_applicable(X, ldx, d) &&
-                             T > skinny_max_tokens();
-    if (staged_path && need > (int64_t)VNM_NOALLOC_SCRATCH_BYTES) {
-      snprintf(g_hip_error, sizeof(g_hip_error),
-               "vnm_spmm_noalloc: %lld tokens x %lld input channels need %lld bytes of staged activations, the "
-               "built-in scratch holds %lld; use vnm_spmm with a workspace",
-               (long long)T, (long long)in, (long long)need, (long long)VNM_NOALLOC_SCRATCH_BYTES);
-      return VNM_ERR_WORKSPACE;
-    }
-  }
-  void* ws = nullptr;
-  if ((rc = noalloc_scratch(&ws)) != VNM_OK) return rc;
-  return spmm_impl(X, T, ldx, values, meta, colidx, packed, out, in, V, N, M, Fused{}, Y, ldy, y_dtype, path, ws,
-                   (int64_t)VNM_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int vnm_spmm_fused(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta,

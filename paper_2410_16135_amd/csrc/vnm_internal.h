@@ -74,6 +74,16 @@ struct Fused {
 };
 
 void set_hip_error(hipError_t e, const char* where);
+void set_error_text(const char* text);           // what vnm_last_hip_error() returns next (calling thread)
+// Host-side argument checks shared by the entry points (vnm_api.hip, no device code in that file)
+int check_pattern(int64_t out, int64_t in, int V, int N, int M);
+constexpr int kProceed = -1;                     // spmm_validate: arguments are fine and there is work to enqueue
+int spmm_validate(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta, const void* colidx,
+                  const void* packed, int64_t out, int64_t in, int V, int N, int M, const struct Fused& f,
+                  const void* Y, int64_t ldy, int y_dtype, int path, int64_t workspace_bytes);
+int spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, const void* meta, const void* colidx,
+              const void* packed, int64_t out, int64_t in, int V, int N, int M, const struct Fused& f, void* Y,
+              int64_t ldy, int y_dtype, int path, void* workspace, int64_t workspace_bytes, void* stream);
 // Raises a kernel's dynamic-LDS limit to the 160 KiB of a gfx950 CU, once per (kernel, device); thread-safe.
 // Returns a vnm_status.
 int allow_big_lds(const void* kernel, const char* what);

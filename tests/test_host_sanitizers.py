@@ -18,8 +18,9 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
         pytest.skip("hipcc not found")
     csrc = os.path.join(ROOT, "paper_2410_16135_amd", "csrc")
     exe = str(tmp_path / "host_check")
-    cmd = [hipcc, "--cuda-host-only", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
-           "-fno-sanitize-recover=undefined", "-I", os.path.join(ROOT, "include"), "-I", csrc,
+    cmd = [hipcc, "--cuda-host-only", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-I", os.path.join(ROOT, "include"), "-I", csrc,
            os.path.join(csrc, "vnm_api.hip"), os.path.join(csrc, "vnm_lsa.hip"), os.path.join(csrc, "vnm_select.hip"),
            os.path.join(ROOT, "tests", "host_sanitize", "host_check.cpp"), "-o", exe]
     res = subprocess.run(cmd, capture_output=True, text=True, timeout=600)

@@ -14,6 +14,15 @@
 // pair, far below what the streaming rate needs; the transposing staged layout of the many-token
 // kernel would cost a second launch.  For at most 16 tokens a second kernel (further down) keeps the
 // whole slice of X in LDS and uses the registers for a deeper weight stream instead.
+//
+// Measured and dropped: dealing the (row block, K step) pairs out evenly to one workgroup per compute
+// unit and adding the parts up inside the kernel (parts to memory with device-scope stores, one arrival
+// counter per row block, the last workgroup to arrive sums in a fixed order).  It was exact and used all
+// 256 units, but the L2 slices of different XCDs do not snoop each other, so parts and counters travel
+// through memory: store acknowledged, counter returned, parts read back are three dependent round
+// trips of about 2 us each.  16 tokens, 64:2:5, back to back: 4096 x 4096 18.0 us against 11.0 us for
+// one workgroup per row block; 11008 x 4096 21.6 against 12.9; 4096 x 11008 18.3 against 14.4 for
+// split K plus the reduction launch.  A kernel boundary is the cheaper device-wide hand-over here.
 #include "vnm_internal.h"
 
 namespace vnm {

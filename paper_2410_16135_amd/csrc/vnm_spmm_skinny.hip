@@ -35,6 +35,7 @@ typedef unsigned sk_u8 __attribute__((ext_vector_type(8)));
 constexpr int kSkWaves = 8;      // waves per workgroup
 constexpr int kSkSPW = 4;        // K steps per wave and phase, at most
 constexpr int kSkNX = 8;         // 16-byte pieces of X per thread and phase, at most
+constexpr int kSkHalfTileMaxWorkgroups = 256;   // the device's compute units
 
 struct SkinnyArgs {
   const unsigned short* X; int64_t T, ldx, in;
@@ -220,10 +221,17 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
 // the last step), so the compiler can wait for exactly the operand it uses next.
 constexpr int kSkNXR = 18;       // 16-byte pieces of X per thread, at most (16 rows of at most 9216 bytes)
 
-template <bool DUAL>
+// HALF: one workgroup per 32-row tile (blockIdx.z picks the tile of the 64-row block) instead of one per
+// block -- twice the workgroups where a matrix has too few row blocks to occupy the compute units; each
+// fetches the whole slice of X but only its tile's weights.
+template <bool DUAL, bool HALF>
 __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(const SkinnyArgs a) {
   constexpr int AT = 2, TT = 16;
-  constexpr int kSkRing = 8;                         // more (10 fit without spilling) measured no faster
+  constexpr int NT = HALF ? 1 : AT;                  // tiles of this workgroup
+  const int t0 = HALF ? (int)blockIdx.z : 0;         // its first tile
+  // 8 operands ahead: 10 fit without spilling and measured no faster; 13 of one tile's (half as large,
+  // all steps of a wave at 104 K steps) measured slower from HBM (18.0 against 15.9 us on 4096 x 4096)
+  constexpr int kSkRing = 8;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -236,13 +244,13 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
   const int pitch = ncol * 2 + 4;                    // bytes per token row: odd number of dwords
   const int64_t col0 = s_lo * 8 * M;
 
-  struct AOp { uint4 w[AT]; unsigned idx; uint4 pc, pc2; };
+  struct AOp { uint4 w[NT]; unsigned idx; uint4 pc, pc2; };
   const int hB = lane >> 5;
   auto load_a = [&](AOp& o, int64_t s) {
     s = s < S ? s : S - 1;                           // beyond the range: a valid operand that is never used
     const int64_t rs = r * S + s;
 #pragma unroll
-    for (int t = 0; t < AT; ++t) o.w[t] = a.pa[(rs * AT + t) * 64 + lane];
+    for (int t = 0; t < NT; ++t) o.w[t] = a.pa[(rs * AT + t0 + t) * 64 + lane];
     o.idx = ((const unsigned*)a.pidx)[rs * 64 + lane];
     if (DUAL) { o.pc = a.pcol[rs * 4 + hB * 2]; o.pc2 = a.pcol[rs * 4 + hB * 2 + 1]; }
     else o.pc = a.pcol[rs * 2 + hB];
@@ -290,9 +298,9 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
   }
   __syncthreads();
 
-  sk_f16 acc[AT];
+  sk_f16 acc[NT];
 #pragma unroll
-  for (int t = 0; t < AT; ++t)
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int k = 0; k < 16; ++k) acc[t][k] = 0.f;
 
@@ -307,6 +315,23 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
       pc[0][0] = o.pc.x; pc[0][1] = o.pc.y; pc[0][2] = o.pc.z; pc[0][3] = o.pc.w;
     }
     const int ix = (int)o.idx;
+    if (HALF) {
+      // the one tile of this workgroup: its column table (DUAL) or the shared one, its half of the index word
+      const int tb = DUAL ? t0 : 0;
+      sk_u8 bw;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        unsigned v[4];
+#pragma unroll
+        for (int kq = 0; kq < 4; ++kq) v[kq] = *(const unsigned short*)(row + 2 * (((tb ? pc[1][kq] : pc[0][kq]) >> (8 * m)) & 255u));
+        bw[2 * m] = v[0] | (v[1] << 16);
+        bw[2 * m + 1] = v[2] | (v[3] << 16);
+      }
+      const sk_h16 bv = __builtin_bit_cast(sk_h16, bw);
+      if (t0 == 0) acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[0]), bv, acc[0], ix, 0, 0);
+      else acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[0]), bv, acc[0], ix, 0, 1);
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < (DUAL ? 2 : 1); ++t) {
       sk_u8 bw;
@@ -322,7 +347,7 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
       if (!DUAL || t == 0)
         acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[0]), bv, acc[0], ix, 0, 0);
       if (!DUAL || t == 1)
-        acc[1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[1]), bv, acc[1], ix, 0, 1);
+        acc[NT - 1] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(sk_h8, o.w[NT - 1]), bv, acc[NT - 1], ix, 0, 1);
     }
   };
 
@@ -336,19 +361,20 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
   }
   __syncthreads();                                   // every wave is done with X: the reduction reuses its LDS
 
-  constexpr int RW = AT * 32;
+  constexpr int RW = AT * 32;                        // rows of a block
+  constexpr int RT = NT * 32;                        // rows of this workgroup
   float* red = (float*)smem;
   if ((lane & 31) < TT) {
     float* mine = red + ((size_t)wave * TT + (lane & 31)) * (RW + 1);
 #pragma unroll
-    for (int t = 0; t < AT; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int j = 0; j < 16; ++j) mine[t * 32 + 8 * (j >> 2) + 4 * hB + (j & 3)] = acc[t][j];
   }
   __syncthreads();
-  for (int e = tid; e < TT * RW; e += 64 * kSkWaves) {
-    const int tok = e / RW, rw = e - tok * RW;
-    const int64_t o = r * RW + rw;
+  for (int e = tid; e < TT * RT; e += 64 * kSkWaves) {
+    const int tok = e / RT, rw = e - tok * RT;
+    const int64_t o = r * RW + t0 * 32 + rw;
     if (tok < a.T && o < a.out) {
       float sum = 0.f;
 #pragma unroll
@@ -372,11 +398,11 @@ static size_t skinny_resident_lds(int M, int64_t nsz) {
   return lds;
 }
 
-template <bool DUAL>
+template <bool DUAL, bool HALF>
 static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
-  auto kern = spmm_skinny_resident_kernel<DUAL>;
+  auto kern = spmm_skinny_resident_kernel<DUAL, HALF>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
-  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS), dim3(64 * kSkWaves), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS, HALF ? 2u : 1u), dim3(64 * kSkWaves), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
@@ -438,7 +464,10 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
         a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
         a.bias = nullptr; a.perm_out = nullptr;                           // applied by the reduction
       }
-      const int rc = dual ? launch_skinny_resident<true>(a, R, KSr, lds, st) : launch_skinny_resident<false>(a, R, KSr, lds, st);
+      // one workgroup per 32-row tile while even those leave compute units idle
+      const bool half = 2 * R * KSr <= kSkHalfTileMaxWorkgroups;
+      const int rc = dual ? (half ? launch_skinny_resident<true, true>(a, R, KSr, lds, st) : launch_skinny_resident<true, false>(a, R, KSr, lds, st))
+                          : (half ? launch_skinny_resident<false, true>(a, R, KSr, lds, st) : launch_skinny_resident<false, false>(a, R, KSr, lds, st));
       if (rc != VNM_OK || KSr == 1) return rc;
       return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
     }

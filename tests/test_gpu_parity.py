@@ -223,6 +223,9 @@ RESIDENT_X_CASES = [
     # (V = 32), with 128-row blocks, and with K split over 4 and over 16 workgroups
     (8256, 2048, 16, 64, 5), (8256, 2080, 9, 32, 6), (8320, 4104, 13, 128, 8), (4096, 11008, 16, 64, 5),
     (640, 20480, 1, 64, 5),
+    # at most 128 row blocks, K unsplit: one workgroup per 32-row tile -- one column table, two tables (V = 32),
+    # 128-row blocks, and V = 32 with an odd number of 32-row blocks (the last 64-row block has one real tile)
+    (4096, 4096, 16, 64, 5), (4096, 2080, 9, 32, 6), (2048, 4104, 13, 128, 8), (2080, 2048, 7, 32, 5),
 ]
 
 

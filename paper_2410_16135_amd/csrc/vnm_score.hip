@@ -16,50 +16,56 @@ __device__ __forceinline__ unsigned long long sc_fp16_units(unsigned short h) {
   return e ? ((unsigned long long)(1024u + m) << (e - 1)) : (unsigned long long)m;
 }
 
-__global__ void __launch_bounds__(256) fill_u64_kernel(unsigned long long* p, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = 0ull;
-}
-
-// Column sums: a workgroup covers 512 columns x kSumRows rows.  Thread (c, q) owns 8 adjacent columns
-// (one 16-byte load per row) and the rows q, q + 4, ... of the strip; the four partial sums of a
-// column chunk meet in LDS and go to global memory with 64-bit integer atomics (exact, so the order
-// is immaterial).  `vec` = rows are 16-byte aligned; otherwise 2-byte loads.
-constexpr int kSumRows = 128;
+// Column sums: a workgroup owns 64 columns and walks all rows.  Thread (c, q) owns 8 adjacent columns
+// (one 16-byte load per row: with 8 such threads a row of the strip is one 128-byte line) and the rows
+// q, q + 32, ...; the 32 partial sums of a column meet in LDS and one thread stores their total, so
+// every sum is written once, by one thread, without atomics.  `vec` = rows are 16-byte aligned;
+// otherwise 2-byte loads.
 __global__ void __launch_bounds__(256)
 abs_colsum_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, int64_t ldw, int vec,
                   unsigned long long* __restrict__ colsum) {
-  __shared__ unsigned long long part[4][64][8];
-  const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int64_t col = ((int64_t)blockIdx.x * 64 + c) * 8;
-  const int64_t row0 = (int64_t)blockIdx.y * kSumRows;
+  __shared__ unsigned long long part[32][8][8];
+  const int c = threadIdx.x & 7, q = threadIdx.x >> 3;
+  const int64_t col = ((int64_t)blockIdx.x * 8 + c) * 8;
   const int nc = col >= in ? 0 : (int)((in - col) < 8 ? (in - col) : 8);
   unsigned long long acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const int64_t row1 = row0 + kSumRows < out ? row0 + kSumRows : out;
-  if (nc > 0)
-    for (int64_t row = row0 + q; row < row1; row += 4) {
-      const unsigned short* p = W + row * ldw + col;
-      if (vec && nc == 8) {
-        const uint4 v = *(const uint4*)p;
-        const unsigned d[4] = {v.x, v.y, v.z, v.w};
+  if (nc > 0) {
+    if (vec && nc == 8) {
+      constexpr int kU = 4;                                   // rows in flight per thread
+      for (int64_t row = q; row < out; row += 32 * kU) {
+        uint4 v[kU];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[2 * e] += sc_fp16_units((unsigned short)(d[e] & 0xFFFFu));
-          acc[2 * e + 1] += sc_fp16_units((unsigned short)(d[e] >> 16));
+        for (int u = 0; u < kU; ++u) {
+          const int64_t rr = row + 32 * u;
+          v[u] = rr < out ? *(const uint4*)(W + rr * ldw + col) : make_uint4(0, 0, 0, 0);
         }
-      } else {
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+          const unsigned d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += sc_fp16_units((unsigned short)(d[e] & 0xFFFFu));
+            acc[2 * e + 1] += sc_fp16_units((unsigned short)(d[e] >> 16));
+          }
+        }
+      }
+    } else {
+      for (int64_t row = q; row < out; row += 32) {
+        const unsigned short* p = W + row * ldw + col;
         for (int e = 0; e < nc; ++e) acc[e] += sc_fp16_units(p[e]);
       }
     }
+  }
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[q][c][e] = acc[e];
   __syncthreads();
-  // 512 column sums of the strip, two per thread
-  for (int i = threadIdx.x; i < 512; i += 256) {
-    const int cc = i >> 3, e = i & 7;
-    const int64_t gc = (int64_t)blockIdx.x * 512 + i;
-    const unsigned long long t = part[0][cc][e] + part[1][cc][e] + part[2][cc][e] + part[3][cc][e];
-    if (gc < in && t) atomicAdd(colsum + gc, t);
+  if (threadIdx.x < 64) {
+    const int cc = threadIdx.x >> 3, e = threadIdx.x & 7;
+    const int64_t gc = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    unsigned long long t = 0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) t += part[k][cc][e];
+    if (gc < in) colsum[gc] = t;
   }
 }
 
@@ -130,13 +136,12 @@ ria_score_kernel(const unsigned short* __restrict__ W, int64_t out, int64_t in, 
 
 int launch_ria_scores(const void* W, int64_t out, int64_t in, int64_t ldw, const void* act, void* S,
                       int64_t lds, void* workspace, hipStream_t st) {
-  if ((out + kSumRows - 1) / kSumRows > 65535 || (out + 3) / 4 > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
+  if ((in + 63) / 64 > 0x7FFFFFFF || (out + 3) / 4 > 0x7FFFFFFF) return VNM_ERR_UNSUPPORTED;
   unsigned long long* colsum = (unsigned long long*)workspace;
   unsigned long long* rowsum = colsum + in;
   const int vec = (ldw % 8 == 0) && (((uintptr_t)W & 15) == 0);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((in + 255) / 256)), dim3(256), 0, st, colsum, in);
-  hipLaunchKernelGGL(abs_colsum_kernel, dim3((unsigned)((in + 511) / 512), (unsigned)((out + kSumRows - 1) / kSumRows)),
-                     dim3(256), 0, st, (const unsigned short*)W, out, in, ldw, vec, colsum);
+  hipLaunchKernelGGL(abs_colsum_kernel, dim3((unsigned)((in + 63) / 64)), dim3(256), 0, st, (const unsigned short*)W, out, in,
+                     ldw, vec, colsum);
   hipLaunchKernelGGL(abs_rowsum_kernel, dim3((unsigned)((out + 3) / 4)), dim3(256), 0, st, (const unsigned short*)W,
                      out, in, ldw, vec, rowsum);
   const int vec_s = (ldw % 4 == 0) && (((uintptr_t)W & 7) == 0) && (lds % 4 == 0) && (((uintptr_t)S & 15) == 0);

@@ -453,6 +453,21 @@ def test_ria_prune_llama_shaped_layer_full_size():
     _check_compressed_scored(c, W, S_ref, layer.V, layer.M)
 
 
+@pytest.mark.parametrize("name", ["gate", "down"])
+def test_ria_scores_of_the_wide_and_tall_layers_are_exact_and_repeatable(name):
+    """11008 x 4096 and 4096 x 11008: more workgroups than compute units in every kernel of the score
+    path.  The scores equal the oracle's bit for bit on every call (three calls on the same inputs)."""
+    layer = [l for l in syn.config_llama2_7b() if l.name == name][0]
+    W, X = syn.layer_tensors(layer, tokens=64)
+    act = np.sqrt((X.astype(np.float64) ** 2).sum(axis=0)).astype(np.float32) ** np.float32(0.5)
+    S_ref = orc.importance_ria(W, act).view(np.uint32)
+    Wd, ad = _dev(W), _dev(act)
+    for _ in range(3):
+        S = vnm.vnm_ria_scores(Wd, ad)
+        torch.cuda.synchronize()
+        assert np.array_equal(S.cpu().numpy().view(np.uint32), S_ref)
+
+
 @pytest.mark.parametrize("out,inn,V,M", [(96, 160, 32, 5), (160, 256, 32, 8), (200, 128, 64, 6), (130, 320, 128, 7),
                                          (32, 64, 32, 4)])
 def test_pack_from_triple_equals_fused_copy(out, inn, V, M):

@@ -335,12 +335,19 @@ int vnm_retained_score(const void* S, int64_t out, int64_t in, int64_t lds, int 
 
 /*
  * Host only.  Linear sum assignment (Section 4.2: every half-step of the permutation search is
- * modelled as one and solved by the Hungarian algorithm): assign[i] = the column given to row i such
- * that sum_i gain[i, assign[i]] is maximal; *total = that sum.  gain: int64 [n x n], row-major,
- * entries in [0, 2^60]; assign: int32 [n].  Exact integer arithmetic, O(n^3).  Among equally good
- * assignments which one is returned is unspecified.
+ * modelled as one and solved exactly; the paper names the Hungarian algorithm): assign[i] = the
+ * column given to row i such that sum_i gain[i, assign[i]] is maximal; *total = that sum.  gain:
+ * int64 [n x n], row-major, entries in [0, 2^60]; assign: int32 [n].  Exact integer arithmetic.
+ * Among equally good assignments which one is returned is unspecified (and differs between the
+ * methods).  vnm_lsa_max = vnm_lsa_max_method with VNM_LSA_AUTO: an auction with epsilon scaling,
+ * and the Hungarian method (O(n^3)) where the auction gives up (values beyond about 2^60 / n, or a
+ * bid budget of 2000 n spent).  VNM_LSA_HUNGARIAN and VNM_LSA_AUCTION force one of them; the
+ * auction alone returns VNM_ERR_UNSUPPORTED where it gives up.  VNM_LSA_AUCTION_SCALAR is the
+ * auction without its AVX-512 row scan (same bids, same result; for checking one against the other).
  */
+enum vnm_lsa_method { VNM_LSA_AUTO = 0, VNM_LSA_HUNGARIAN = 1, VNM_LSA_AUCTION = 2, VNM_LSA_AUCTION_SCALAR = 3 };
 int vnm_lsa_max(const void* gain, int n, void* assign, int64_t* total);
+int vnm_lsa_max_method(const void* gain, int n, int method, void* assign, int64_t* total);
 
 const char* vnm_status_string(int status);
 /* Text of the last HIP error seen by the calling thread ("" if none). */

@@ -74,6 +74,8 @@ def load_library():
     lib.vnm_lora_merge.restype = ci
     lib.vnm_lsa_max.argtypes = [vp, ci, vp, ctypes.POINTER(i64)]
     lib.vnm_lsa_max.restype = ci
+    lib.vnm_lsa_max_method.argtypes = [vp, ci, ci, vp, ctypes.POINTER(i64)]
+    lib.vnm_lsa_max_method.restype = ci
     lib.vnm_fold_permutations.argtypes = [vp, vp, i64, vp]
     lib.vnm_fold_permutations.restype = ci
     lib.vnm_decompress.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, i64, vp]

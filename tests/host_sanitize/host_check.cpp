@@ -71,6 +71,10 @@ int main() {
       int64_t tot = -1;
       CHECK(vnm_lsa_max(g.data(), n, as.data(), &tot) == VNM_OK);
       CHECK(tot == brute_force(g, n));
+      { std::vector<int> as2((size_t)n, -1); int64_t t2 = -1;
+        CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_HUNGARIAN, as2.data(), &t2) == VNM_OK && t2 == tot);
+        CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_AUCTION, as2.data(), &t2) == VNM_OK && t2 == tot);
+        CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_AUCTION_SCALAR, as2.data(), &t2) == VNM_OK && t2 == tot); }
       std::vector<char> seen((size_t)n, 0);
       int64_t sum = 0;
       for (int i = 0; i < n; ++i) { CHECK(as[(size_t)i] >= 0 && as[(size_t)i] < n && !seen[(size_t)as[(size_t)i]]); seen[(size_t)as[(size_t)i]] = 1; sum += g[(size_t)i * n + as[(size_t)i]]; }
@@ -87,6 +91,10 @@ int main() {
     int64_t sum = 0, ident = 0;
     for (int i = 0; i < n; ++i) { CHECK(as[(size_t)i] >= 0 && as[(size_t)i] < n && !seen[(size_t)as[(size_t)i]]); seen[(size_t)as[(size_t)i]] = 1; sum += g[(size_t)i * n + as[(size_t)i]]; ident += g[(size_t)i * n + i]; }
     CHECK(sum == tot && tot >= ident);
+    { std::vector<int> as2((size_t)n, -1); int64_t t2 = -1;       // both methods, same optimum
+      CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_HUNGARIAN, as2.data(), &t2) == VNM_OK && t2 == tot);
+      CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_AUCTION, as2.data(), &t2) == VNM_OK && t2 == tot);
+      CHECK(vnm_lsa_max_method(g.data(), n, VNM_LSA_AUCTION_SCALAR, as2.data(), &t2) == VNM_OK && t2 == tot); }
   }
   { int64_t bad[4] = {1, -1, 2, 3}; int as[2]; int64_t tot; CHECK(vnm_lsa_max(bad, 2, as, &tot) == VNM_ERR_SHAPE); CHECK(vnm_lsa_max(nullptr, 2, as, &tot) == VNM_ERR_NULL); CHECK(vnm_lsa_max(bad, 0, as, &tot) == VNM_ERR_SHAPE); }
   // ---- V/M selection

@@ -135,6 +135,75 @@ def test_library_assignment_matches_oracle_value(lib, n, kind):
     assert total == orc.lsa_max(gain)[1]
 
 
+def _lib_lsa_method(lib, gain, method):
+    g = np.ascontiguousarray(gain, dtype=np.int64)
+    n = g.shape[0]
+    assign = np.full(n, -1, dtype=np.int32)
+    total = ctypes.c_int64(0)
+    rc = lib.vnm_lsa_max_method(g.ctypes.data_as(ctypes.c_void_p), n, method, assign.ctypes.data_as(ctypes.c_void_p),
+                                ctypes.byref(total))
+    return rc, assign, total.value
+
+
+LSA_AUTO, LSA_HUNGARIAN, LSA_AUCTION, LSA_AUCTION_SCALAR = 0, 1, 2, 3
+
+
+def _search_like_gain(n, seed):
+    """A gain matrix with the structure the search produces: every row prefers the same few columns
+    (block k gains max(0, x_i - t_k) summed over rows of the matrix), all values distinct or not."""
+    rng = np.random.default_rng(seed)
+    x = rng.integers(0, 2 ** 20, size=(n, 32))            # lifted channel i, 32 row blocks
+    t = rng.integers(0, 2 ** 20, size=(n, 32))            # threshold of block k per row block
+    base = rng.integers(2 ** 30, 2 ** 31, size=n)
+    return base[None, :] + np.maximum(0, x[:, None, :] - t[None, :, :]).sum(axis=2)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 17, 64, 200])
+@pytest.mark.parametrize("kind", ["random", "ties", "large", "search"])
+def test_auction_and_hungarian_agree_with_the_oracle(lib, n, kind):
+    """Two independent exact methods of the library and the oracle's solver reach the same optimum;
+    each returned assignment is a permutation that attains it."""
+    rng = np.random.default_rng(100 + n)
+    if kind == "search":
+        gain = _search_like_gain(n, n)
+    else:
+        gain = rng.integers(0, {"random": 10 ** 6, "ties": 4, "large": 2 ** 45}[kind], size=(n, n))
+    want = orc.lsa_max(gain)[1]
+    got = {}
+    for method in (LSA_HUNGARIAN, LSA_AUCTION, LSA_AUCTION_SCALAR, LSA_AUTO):
+        rc, assign, total = _lib_lsa_method(lib, gain, method)
+        assert rc == 0
+        assert sorted(assign) == list(range(n))
+        assert total == sum(int(gain[i, assign[i]]) for i in range(n)) == want
+        got[method] = assign
+    # the vector row scan and the scalar one make the same bids, so even among ties the same assignment
+    assert np.array_equal(got[LSA_AUCTION], got[LSA_AUCTION_SCALAR])
+    assert np.array_equal(got[LSA_AUCTION], got[LSA_AUTO])
+
+
+def test_auction_brute_force_small(lib):
+    """The auction against enumeration of all permutations, ties included."""
+    import itertools
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        n = int(rng.integers(2, 7))
+        gain = rng.integers(0, 6 if trial % 2 else 1000, size=(n, n))
+        best = max(sum(int(gain[i, p[i]]) for i in range(n)) for p in itertools.permutations(range(n)))
+        rc, assign, total = _lib_lsa_method(lib, gain, LSA_AUCTION)
+        assert rc == 0 and total == best and sorted(assign) == list(range(n))
+
+
+def test_auction_gives_up_on_values_it_cannot_scale(lib):
+    """Gains near 2^60 times n + 1 do not fit 62 bits: the auction alone refuses, the default falls
+    back to the Hungarian method and is still exact."""
+    rng = np.random.default_rng(9)
+    gain = rng.integers(2 ** 59, 2 ** 60, size=(8, 8))
+    assert _lib_lsa_method(lib, gain, LSA_AUCTION)[0] == 3          # VNM_ERR_UNSUPPORTED
+    rc, assign, total = _lib_lsa_method(lib, gain, LSA_AUTO)
+    assert rc == 0 and total == orc.lsa_max(gain)[1]
+    assert _lib_lsa_method(lib, gain, 7)[0] == 3                    # unknown method
+
+
 def test_library_assignment_errors(lib):
     assert lib.vnm_lsa_max(None, 3, None, None) == 1
     g = np.zeros((2, 2), dtype=np.int64)

@@ -690,8 +690,8 @@ def main():
             "layer": L.name, "iterations": 1, "seconds": time.time() - t0,
             "objective": [int(h) for h in hist],
             "retained_gain_percent": 100.0 * float(hist[-1] - hist[0]) / float(hist[0]),
-            "note": "wall time incl. the host assignment solver (5 problems of 819 x 819, 64 of 64 x 64), "
-                    "which takes most of it; device kernels about 25 ms"}
+            "note": "wall time incl. the host assignment solver (auction with epsilon scaling; 5 problems of 819 x 819, "
+                    "64 of 64 x 64); device kernels about 25 ms"}
         result["beyond_hot_path"] = {
             "layer": L.name, "ria_scores_ms": t_ria, "prune_compress_scored_ms": t_ps,
             "ria_scores_gbps": (2 * w_bytes + 2 * w_bytes) / t_ria / 1e6,

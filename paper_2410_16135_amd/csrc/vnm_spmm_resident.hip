@@ -83,26 +83,46 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
   const int64_t rb_hi = rb_lo + a.rb_per < a.R ? rb_lo + a.rb_per : a.R;
   constexpr int kBatch = kResWaves * RPW;                   // row blocks the workgroup holds at a time
   const int nbatch = (int)((rb_hi - rb_lo + kBatch - 1) / kBatch);
-  const int nseg = nchunks * RPW;                           // segments (chunk, held row block) of a batch
 
   // A wave's work is a list of segments -- batch by batch, chunk by chunk, held row block by held
   // row block -- of csz K steps each, padded to a multiple of the ring size so that step i of a
   // segment always sits in ring slot i % RING (slots are registers, their index must be a
   // constant).  Padding steps are loaded like real ones (from a valid address) and never multiplied.
   struct AOp { uint4 w[2]; unsigned idx; unsigned pc[NT]; };
-  // operand of step i of segment sg of batch bt; every load is unconditional, indices beyond the
-  // ends are clamped to valid ones
-  auto load_a = [&](AOp& o, int bt, int sg, int i) {
-    const int c = RPW == 2 ? sg >> 1 : sg, r = RPW == 2 ? sg & 1 : 0;
-    int64_t rb = rb_lo + (int64_t)bt * kBatch + r * kResWaves + wave;
+  // Operands are requested in exactly the order the steps are multiplied in, RING steps ahead, by a
+  // cursor of scalars: (batch, chunk, held row block, step) and, per segment, the number of the
+  // segment's first (row block, K step) pair in the packed copy and of the row block's last one.  A
+  // step costs an add and a minimum; the multiplications happen once per segment.  Every load is
+  // unconditional, pairs beyond the ends are clamped to valid ones.  32-bit byte offsets: the plan
+  // admits at most 2^21 (row block, K step) pairs of 2 KiB.
+  int l_bt = 0, l_c = 0, l_r = 0, l_step = 0;
+  unsigned l_base = 0, l_lim = 0;
+  auto seg_setup = [&]() {
+    int64_t rb = rb_lo + (int64_t)l_bt * kBatch + l_r * kResWaves + wave;
     rb = rb < a.R ? rb : a.R - 1;
-    const int64_t s = (int64_t)c * csz + i;
-    const int64_t rs = rb * a.S + (s < a.S ? s : a.S - 1);
-    o.w[0] = a.pa[(rs * 2) * 64 + lane];
-    o.w[1] = a.pa[(rs * 2 + 1) * 64 + lane];
-    o.idx = a.pidx[rs * 64 + lane];
+    l_base = (unsigned)(rb * a.S + (int64_t)l_c * csz);
+    l_lim = (unsigned)(rb * a.S + a.S - 1);
+  };
+  seg_setup();
+  const unsigned lane_a = (unsigned)lane * 16u, lane_i = (unsigned)lane * 4u;
+  const unsigned lane_c = (unsigned)((hB * 4 + kq) * NT) * 4u;
+  auto load_next = [&](AOp& o) {
+    unsigned rs = l_base + (unsigned)l_step;
+    rs = rs < l_lim ? rs : l_lim;
+    const char* pw = (const char*)a.pa + (rs * 2048u + lane_a);
+    o.w[0] = *(const uint4*)pw;
+    o.w[1] = *(const uint4*)(pw + 1024);
+    o.idx = *(const unsigned*)((const char*)a.pidx + (rs * 256u + lane_i));
 #pragma unroll
-    for (int t = 0; t < NT; ++t) o.pc[t] = a.pcol[(rs * 8 + hB * 4 + kq) * NT + t];
+    for (int t = 0; t < NT; ++t) o.pc[t] = *(const unsigned*)((const char*)a.pcol + (rs * (unsigned)(32 * NT) + lane_c + 4u * t));
+    if (++l_step == csz_p) {
+      l_step = 0;
+      if (++l_r == RPW) {
+        l_r = 0;
+        if (++l_c == nchunks) { l_c = 0; ++l_bt; }
+      }
+      seg_setup();
+    }
   };
   AOp ring[RING];
 
@@ -158,7 +178,7 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
   if constexpr (CHUNKED) {
     x_load(xn, 0, 0);
 #pragma unroll
-    for (int i = 0; i < RING; ++i) load_a(ring[i], 0, 0, i);
+    for (int i = 0; i < RING; ++i) load_next(ring[i]);
     x_park(xn, 0, 0, 0);
     if (nimg > 1) x_load(xn, 1, 0);                         // under the first chunk's multiplications
   } else {
@@ -166,7 +186,7 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
     uint4 xw[NX];
     x_load(xw, 0, 0);
 #pragma unroll
-    for (int i = 0; i < RING; ++i) load_a(ring[i], 0, 0, i);
+    for (int i = 0; i < RING; ++i) load_next(ring[i]);
     x_park(xw, 0, 0, 0);
     for (int first = NX; first < npieces; first += NX) {
       x_load(xw, 0, first);
@@ -188,7 +208,8 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
   };
 
   const unsigned lds0 = (unsigned)(size_t)(VNM_RS_LDS(unsigned char))smem;
-  // one K step: ls = step within the image at byte offset buf
+  // one K step: ls = step within the image at byte offset buf; per token half, four transposing reads
+  // at the rows the packed table names, and their matrix instructions
   auto compute = [&](rs_f16 (&ac)[2][2], const AOp& o, unsigned buf, int ls) {
     const int ix = (int)o.idx;
     const unsigned base = lds0 + buf + (unsigned)(ls * 8 * M) * (unsigned)P + tokoff;
@@ -196,7 +217,7 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
     for (int t = 0; t < NT; ++t) {
       unsigned row[4];
 #pragma unroll
-      for (int m = 0; m < 4; ++m) row[m] = base + ((o.pc[t] >> (8 * m)) & 255u) * (unsigned)P;
+      for (int m = 0; m < 4; ++m) row[m] = base + __umul24((o.pc[t] >> (8 * m)) & 255u, (unsigned)P);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         rs_s4 b4[4];
@@ -309,6 +330,11 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
   };
 
   // ---- the loops
+  // (Reading the next step's B operands from LDS ahead of the current step's matrix instructions, with
+  // a second set of operand registers, measured no faster: 81.9 against 80.7 us over a DeiT-small
+  // block.  What a step used to wait for was the scalar unit, shared by the CU's 8 waves: the address
+  // arithmetic of the operand loads, about 45 scalar instructions per wave and step before the
+  // cursor above, took more of it than the four matrix instructions take of a SIMD.)
   int img = 0;                                              // image being multiplied
   for (int bt = 0; bt < nbatch; ++bt) {
     zero_acc();
@@ -318,16 +344,13 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
       const int nsc = (int)(sleft < csz ? sleft : csz);     // real steps of this chunk
 #pragma unroll
       for (int r = 0; r < RPW; ++r) {
-        const int sg = c * RPW + r;
-        const bool more = sg + 1 < nseg;                    // where the ring is refilled from once this segment runs out
         const int64_t rb = rb_lo + (int64_t)bt * kBatch + r * kResWaves + wave;
+        const bool mine = rb < rb_hi;
         for (int i0 = 0; i0 < csz_p; i0 += RING) {
 #pragma unroll
           for (int i = 0; i < RING; ++i) {
-            if (i0 + i < nsc && rb < rb_hi) compute(acc[r], ring[i], buf, i0 + i);
-            const bool wrap = i0 + i + RING >= csz_p;
-            load_a(ring[i], wrap && !more ? bt + 1 : bt, wrap ? (more ? sg + 1 : 0) : sg,
-                   wrap ? i0 + i + RING - csz_p : i0 + i + RING);
+            if (i0 + i < nsc && mine) compute(acc[r], ring[i], buf, i0 + i);
+            load_next(ring[i]);
           }
         }
       }
@@ -364,7 +387,7 @@ static ResPlan resident_plan(int64_t T, const Dims& d) {
   if (!has_packed(d.V, d.M) || T <= 0) return p;
   const int64_t R = packed_row_blocks(d);
   p.tiles = (T + kResTok - 1) / kResTok;
-  if (p.tiles > 0x7FFFFFFF) return p;
+  if (p.tiles > 0x7FFFFFFF || R * d.S > ((int64_t)1 << 21)) return p;    // the kernel addresses the packed copy with 32-bit offsets
   const int64_t rows_per_step = 8 * d.M;
   const size_t strips = (size_t)kResWaves * kResEpBytes;
   const size_t room = 160 * 1024 - 64 - strips;             // LDS left for images next to the epilogue strips

@@ -23,6 +23,16 @@
 // trips of about 2 us each.  16 tokens, 64:2:5, back to back: 4096 x 4096 18.0 us against 11.0 us for
 // one workgroup per row block; 11008 x 4096 21.6 against 12.9; 4096 x 11008 18.3 against 14.4 for
 // split K plus the reduction launch.  A kernel boundary is the cheaper device-wide hand-over here.
+//
+// Also measured and dropped, for up to 16 tokens: the slice of X transposed into LDS ([raw column][16
+// tokens], 32 bytes per column, one row left empty after every 8) and the B operand fetched with four
+// transposing reads per step as in the many-token kernels, instead of 16 two-byte reads.  The steps got
+// shorter (3.8 -> 3.2 us for the 13 steps of a wave; what they wait for is mostly the second round of
+// weight loads, not their own instructions), but parking X took longer than it saved (3.8 -> 5.9 us
+// with two-byte stores, more with pairs of lanes exchanging halves to store dwords): 12.6 against
+// 11.6 us on 4096 x 4096, 14.1 against 13.0 us on 11008 x 4096.  A ring of 13 operands (every weight
+// of a wave requested before X is complete) made it worse still: the weights crowd out the loads of X
+// that the barrier waits for.
 #include "vnm_internal.h"
 
 namespace vnm {

@@ -9,32 +9,39 @@
 
 namespace vnm {
 
-// |w| of an fp16 bit pattern as a double.  A column sum of up to 128 such terms spans fewer than 53
-// bits, so every partial sum is exact in fp64 and the order of additions does not matter.
+// |w| of the fp16 bit pattern in the low half of h as a double (the high half is ignored).  The sign
+// is dropped on the fp32 value, where it is an operand modifier of the second conversion and costs
+// no instruction; the empty asm keeps the compiler from moving it back in front of the first one,
+// where it would be a mask.  A column sum of up to 128 such terms spans fewer than 53 bits, so every
+// partial sum is exact in fp64 and the order of additions does not matter.
 __device__ __forceinline__ double fp16_abs_f64(unsigned h) {
-  const unsigned short b = (unsigned short)(h & 0x7FFFu);
+  const unsigned short b = (unsigned short)h;
   _Float16 f;
   __builtin_memcpy(&f, &b, 2);
-  return (double)f;
+  float t = (float)f;
+  asm("" : "+v"(t));
+  return (double)__builtin_fabsf(t);
 }
 
 // Two largest magnitudes of four, ties to the lower position (Section 3, row-wise N:4 step).
-// Each candidate becomes the key (magnitude, 3 - position, sign): distinct keys, larger is better.
+// w0..w3 are fp16 bit patterns (upper halves zero).  Each candidate becomes the key
+// (inverted magnitude | 14 zero bits | position | sign), built with one funnel shift and one XOR:
+// the keys are distinct and the two smallest belong to the two largest magnitudes, the lower
+// position first among equals.  A second funnel shift turns a key into position << 16 | sign << 15 |
+// inverted magnitude, so ordering the two winners by that word orders them by position.
 // Returns positions p0 < p1 as p0 | p1 << 2 and the two kept fp16 patterns in `pair` (p0 low half).
 __device__ __forceinline__ unsigned top2_of_4_f(unsigned w0, unsigned w1, unsigned w2, unsigned w3, unsigned& pair) {
-  const unsigned k0 = ((w0 & 0x7FFFu) << 3) | (3u << 1) | (w0 >> 15);
-  const unsigned k1 = ((w1 & 0x7FFFu) << 3) | (2u << 1) | (w1 >> 15);
-  const unsigned k2 = ((w2 & 0x7FFFu) << 3) | (1u << 1) | (w2 >> 15);
-  const unsigned k3 = ((w3 & 0x7FFFu) << 3) | (0u << 1) | (w3 >> 15);
-  const unsigned a = max(k0, k1), b = min(k0, k1), c = max(k2, k3), d = min(k2, k3);
-  const unsigned m1 = max(a, c);
-  const unsigned m2 = max(max(b, d), min(a, c));
-  const unsigned pa = 3u - ((m1 >> 1) & 3u), pb = 3u - ((m2 >> 1) & 3u);
-  const unsigned va = (m1 >> 3) | ((m1 & 1u) << 15), vb = (m2 >> 3) | ((m2 & 1u) << 15);
-  const bool sw = pa > pb;
-  const unsigned p0 = sw ? pb : pa, p1 = sw ? pa : pb;
-  pair = sw ? (vb | (va << 16)) : (va | (vb << 16));
-  return p0 | (p1 << 2);
+  const unsigned k0 = __builtin_amdgcn_alignbit(w0, w0, 15) ^ 0xFFFE0000u;
+  const unsigned k1 = __builtin_amdgcn_alignbit(w1, w1, 15) ^ 0xFFFE0002u;
+  const unsigned k2 = __builtin_amdgcn_alignbit(w2, w2, 15) ^ 0xFFFE0004u;
+  const unsigned k3 = __builtin_amdgcn_alignbit(w3, w3, 15) ^ 0xFFFE0006u;
+  const unsigned a = min(k0, k1), b = max(k0, k1), c = min(k2, k3), d = max(k2, k3);
+  const unsigned m1 = min(a, c);
+  const unsigned m2 = min(min(b, d), max(a, c));
+  const unsigned e1 = __builtin_amdgcn_alignbit(m1, m1, 17), e2 = __builtin_amdgcn_alignbit(m2, m2, 17);
+  const unsigned lo = min(e1, e2), hi = max(e1, e2);
+  pair = __builtin_amdgcn_perm(hi, lo, 0x05040100u) ^ 0x7FFF7FFFu;
+  return (lo >> 16) | ((hi >> 16) << 2);
 }
 
 // The same selection on importance scores handed in (finite, non-negative fp32, compared through
@@ -100,14 +107,18 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.0;
     constexpr int kBatch = 12;
+    // rows of this tile that exist in W (none when the 8 columns lie beyond the last one)
+    const int64_t rows_left = a.out - r * V;
+    const int v_real = !col_ok || rows_left <= 0 ? 0 : (rows_left < V ? (int)rows_left : V);
+    const char* src = (const char*)(a.W + (r * V + g) * a.ldw + col);
+    const int64_t row_step = (int64_t)G * a.ldw * 2;
     for (int v = g; v < V; v += kBatch * G) {
       uint4 w[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
-        const int vv = v + u * G;
-        const int64_t row = r * V + vv;
         w[u] = make_uint4(0, 0, 0, 0);
-        if (vv < V && row < a.out && col_ok) w[u] = *(const uint4*)(a.W + row * a.ldw + col);
+        if (v + u * G < v_real) w[u] = *(const uint4*)src;
+        src += row_step;
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
@@ -118,7 +129,7 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
           if constexpr (!SCORED) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              acc[2 * e] += fp16_abs_f64(d[e] & 0xFFFFu);
+              acc[2 * e] += fp16_abs_f64(d[e]);
               acc[2 * e + 1] += fp16_abs_f64(d[e] >> 16);
             }
           }

@@ -68,7 +68,7 @@ struct PruneFastArgs {
   const float* Sc; int64_t lds_s;                    // importance scores (SCORED instantiation only)
 };
 
-// LDS layout (dynamic): tile u16 [V][NCP] | tot f64 [NC] | keep u32 [NBW] | (SCORED) scores f32 [V][NC + 4]
+// LDS layout (dynamic): tile u16 [V][NCP = NC + 4] | tot f64 [NC] | keep u32 [NBW] | (SCORED) scores f32 [V][NC + 4]
 // SCORED: the selections are driven by the score matrix a.Sc instead of |w| (Section 3, steps 2-3 on
 // any importance score, e.g. RIA, Eq. 1): column norms are the fp64 sums of the scores added in row
 // order (their value can depend on the order, so it is fixed), step 3 compares the scores; the kept
@@ -84,7 +84,9 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
   const int64_t c0 = s_begin * 8 * M;
   const int64_t b0 = s_begin * 8;
   const int nbw = (int)((a.B - b0) < nks * 8 ? (a.B - b0) : nks * 8);   // real blocks here
-  const int NCP = NC + 8;                           // tile pitch in elements (16-byte rows, skewed banks)
+  // tile pitch in elements: 8-byte rows, and a number of dwords that is 2 mod 4, so that the same
+  // column of 32 consecutive rows lies in 32 different banks (phase 2 walks the tile that way)
+  const int NCP = NC + 4;
   const int G = a.G;
   unsigned short* tile = (unsigned short*)smem;
   double* tot = (double*)(smem + (size_t)V * NCP * 2);
@@ -96,7 +98,7 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
 
   for (int c = tid; c < NC; c += 256) tot[c] = 0.0;
   __syncthreads();
-  // phase 0: W tile -> LDS with 16-byte accesses (zero where W is padded); the same registers feed
+  // phase 0: W tile -> LDS, 16 bytes per load and two 8-byte halves per store (zero where W is padded); the same registers feed
   // the column sums: thread (g, ch) owns 8 columns and the rows g, g + G, g + 2G, ...; the partial
   // sums meet in LDS by atomic adds (exact, so their order is immaterial)
   if (tid < chunks * G) {
@@ -110,21 +112,31 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
     // rows of this tile that exist in W (none when the 8 columns lie beyond the last one)
     const int64_t rows_left = a.out - r * V;
     const int v_real = !col_ok || rows_left <= 0 ? 0 : (rows_left < V ? (int)rows_left : V);
-    const char* src = (const char*)(a.W + (r * V + g) * a.ldw + col);
-    const int64_t row_step = (int64_t)G * a.ldw * 2;
-    for (int v = g; v < V; v += kBatch * G) {
+    // a load address is a base that is the same for the whole workgroup (row r V + vb + u G, column
+    // c0) plus this thread's place in the group of G rows, 32 bits: no 64-bit vector arithmetic
+    const unsigned lane_off = ((unsigned)g * (unsigned)a.ldw + (unsigned)ch * 8u) * 2u;
+    const char* tile_src = (const char*)(a.W + r * V * a.ldw + c0);
+    for (int vb = 0; vb < V; vb += kBatch * G) {
+      const int v = vb + g;
       uint4 w[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
+        // (the row's byte offset goes through readfirstlane so that the multiplication stays on the
+        // scalar unit instead of becoming a 64-bit vector multiply-add per load)
+        const uint64_t ro = (uint64_t)((int64_t)(vb + u * G) * a.ldw * 2);
+        const uint64_t ro_s = ((uint64_t)__builtin_amdgcn_readfirstlane((unsigned)(ro >> 32)) << 32) |
+                              __builtin_amdgcn_readfirstlane((unsigned)ro);
+        const char* row_src = tile_src + ro_s;
         w[u] = make_uint4(0, 0, 0, 0);
-        if (v + u * G < v_real) w[u] = *(const uint4*)src;
-        src += row_step;
+        if (v + u * G < v_real) w[u] = *(const uint4*)(row_src + lane_off);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int vv = v + u * G;
         if (vv < V) {
-          *(uint4*)(tile + (size_t)vv * NCP + ch * 8) = w[u];
+          uint2* td = (uint2*)(tile + (size_t)vv * NCP + ch * 8);
+          td[0] = make_uint2(w[u].x, w[u].y);
+          td[1] = make_uint2(w[u].z, w[u].w);
           const unsigned d[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
           if constexpr (!SCORED) {
 #pragma unroll
@@ -329,12 +341,13 @@ static int prune_fast_ksw(const Dims& d) {
 
 static size_t prune_fast_lds(int V, int M, int KSW, bool scored = false) {
   const size_t NC = (size_t)KSW * 8 * M, NBW = (size_t)KSW * 8;
-  return (size_t)V * (NC + 8) * 2 + NC * 8 + NBW * 4 + (scored ? (size_t)V * (NC + 4) * 4 : 0);
+  return (size_t)V * (NC + 4) * 2 + NC * 8 + NBW * 4 + (scored ? (size_t)V * (NC + 4) * 4 : 0);
 }
 
 bool prune_fast_applicable(const void* W, int64_t ldw, const Dims& d, const void* mask) {
+  // ldw: a thread's byte offset inside its workgroup's rows of W is kept in 32 bits
   return d.M <= 16 && d.V % 32 == 0 && d.V <= 128 && d.in % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)W & 15) == 0 &&
-         d.S <= 65535;
+         d.S <= 65535 && ldw < ((int64_t)1 << 24);
 }
 
 // Score-driven variant: the same kernel with the score tile next to the weight tile in LDS

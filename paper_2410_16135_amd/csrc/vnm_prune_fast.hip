@@ -348,11 +348,14 @@ __global__ void __launch_bounds__(256) prune_pack_kernel(const PruneFastArgs a) 
 
 // K steps per workgroup: 8 make every span of columns a whole number of 128-byte lines; fewer when
 // the tile would not leave room for 3 workgroups per CU, or when the launch would be little more
-// than one generation of workgroups on the 256 CUs (then shorter-lived workgroups overlap better).
+// than one generation of workgroups on the 256 CUs (then shorter-lived workgroups overlap better),
+// down to 1 when it would not even be one workgroup per CU (small matrices: the launch then lasts as
+// long as one workgroup lives, and that is proportional to its tile).
 static int prune_fast_ksw(const Dims& d) {
   int k = 8;
   while (k > 1 && (size_t)d.V * (k * 8 * d.M + 8) * 2 > 46 * 1024) k >>= 1;
   while (k > 4 && d.R * ((d.S + k - 1) / k) < 6 * 256) k >>= 1;
+  while (k > 1 && d.R * ((d.S + k - 1) / k) < 256) k >>= 1;
   return k;
 }
 

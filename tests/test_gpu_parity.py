@@ -73,6 +73,24 @@ def test_prune_compress_strided_input_and_degenerate_blocks():
     _check_compressed(c, W, 32, 5)
 
 
+@pytest.mark.parametrize("ldw", [(1 << 23) - 8, 1 << 23])
+def test_prune_compress_at_the_row_pitch_limit_of_the_fast_kernel(ldw):
+    """The one-pass pruning kernel keeps a thread's byte offset inside its workgroup's rows in 32 bits with the
+    row pitch as a 24-bit factor: a pitch just below 2^23 elements still takes it, 2^23 takes the general
+    kernels; both give the oracle's bits.  (130 rows: a full 128-row block and a ragged one.)"""
+    rng = np.random.default_rng(ldw % 1000)
+    out, inn, V, M = 130, 320, 128, 5
+    W = _rand_w(rng, out, inn, "normal")
+    buf = torch.zeros((out - 1) * ldw + inn, dtype=torch.float16, device="cuda:0")
+    Wt = buf.as_strided((out, inn), (ldw, 1))
+    Wt.copy_(torch.from_numpy(W))
+    c = vnm.vnm_prune_compress(Wt, V, M, want_mask=True)
+    torch.cuda.synchronize()
+    values, meta, colidx, mask = _check_compressed(c, W, V, M)
+    Wd = vnm.vnm_decompress(c).cpu().numpy()
+    assert np.array_equal(Wd.view(np.uint16), orc.masked_dense(W, mask).view(np.uint16))
+
+
 SPMM_CASES = [
     # out, in, T, V, M
     (128, 128, 16, 64, 8), (128, 128, 1, 64, 8), (192, 160, 130, 64, 5), (96, 200, 300, 32, 5),

@@ -130,34 +130,37 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
   // load), a wave-wide load covers 8 tokens x 8 chunks of 16 bytes; every lane then stores its 8
   // columns to 8 image rows, two bytes each.  Rows beyond T and columns beyond `in` become zero (the
   // packed copy holds zero weights there, and zero times whatever else LDS held could be NaN).
-  // Image number k (in the order they are needed) is chunk k % nchunks.
   const int tsub = lane >> 3, csub = lane & 7;
-  // pieces [first, first + NX) of this thread for image k: piece n is unit wave + 8 n, unit u =
-  // (chunk group u >> 3, token group u & 7)
-  auto x_load = [&](uint4 (&xw)[NX], int k, int first) {
-    const int c = k % nchunks;
+  // pieces [first, first + NX) of this thread for chunk c: piece n is unit wave + 8 n, unit u =
+  // (chunk group u >> 3, token group u & 7) -- so all pieces of a thread belong to one token, number
+  // wave * 8 + tsub of the tile, and piece n starts (first + n) * 64 + csub * 8 columns into the
+  // chunk's span.  The loads are unconditional (the compiler then knows how many are in flight and
+  // can let the weight operands requested after them stay in flight while X is parked) and cheap to address: one row pointer per thread (a
+  // valid row also for tokens beyond T), a 32-bit column clamped to the last 8 that exist in the span
+  // and in the row; what a clamped piece brings is dropped when it is parked.
+  const int x_tok = wave * 8 + tsub;
+  const unsigned short* x_row = a.X + (t0 + x_tok < a.T ? (t0 + x_tok) * a.ldx : 0);
+  auto x_load = [&](uint4 (&xw)[NX], int c, int first) {
     const int64_t col0 = (int64_t)c * csz * 8 * M;
     const int64_t sleft = a.S - (int64_t)c * csz;
     const int CH = (int)(sleft < csz ? sleft : csz) * M;    // 16-byte chunks per token
+    const int64_t span_end = col0 + (int64_t)CH * 8;
+    const unsigned col_last = (unsigned)((span_end < a.in ? span_end : a.in) - 8);
+    const unsigned col_first = (unsigned)col0 + (unsigned)(csub * 8);
 #pragma unroll
     for (int n = 0; n < NX; ++n) {
-      const int u = wave + kResWaves * (first + n);
-      const int tok = (u & 7) * 8 + tsub, ch = (u >> 3) * 8 + csub;
-      const bool ok = ch < CH && t0 + tok < a.T && col0 + ch * 8 < a.in;
-      const unsigned short* src = ok ? a.X + (t0 + tok) * a.ldx + col0 + ch * 8 : a.X;
-      xw[n] = *(const uint4*)src;
+      const unsigned col = col_first + (unsigned)((first + n) * 64);
+      xw[n] = *(const uint4*)(x_row + (col < col_last ? col : col_last));
     }
   };
-  auto x_park = [&](const uint4 (&xw)[NX], int k, int first, unsigned buf) {
-    const int c = k % nchunks;
+  auto x_park = [&](const uint4 (&xw)[NX], int c, int first, unsigned buf) {
     const int64_t col0 = (int64_t)c * csz * 8 * M;
     const int64_t sleft = a.S - (int64_t)c * csz;
     const int CH = (int)(sleft < csz ? sleft : csz) * M;
     const int CHz = csz * M;                                // a short last chunk is padded with zero rows
 #pragma unroll
     for (int n = 0; n < NX; ++n) {
-      const int u = wave + kResWaves * (first + n);
-      const int tok = (u & 7) * 8 + tsub, ch = (u >> 3) * 8 + csub;
+      const int tok = x_tok, ch = (first + n) * 8 + csub;
       if (ch < CHz) {
         const bool ok = ch < CH && t0 + tok < a.T && col0 + ch * 8 < a.in;
         const uint4 v = ok ? xw[n] : make_uint4(0, 0, 0, 0);
@@ -180,7 +183,7 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
 #pragma unroll
     for (int i = 0; i < RING; ++i) load_next(ring[i]);
     x_park(xn, 0, 0, 0);
-    if (nimg > 1) x_load(xn, 1, 0);                         // under the first chunk's multiplications
+    if (nimg > 1) x_load(xn, nchunks > 1 ? 1 : 0, 0);       // under the first chunk's multiplications
   } else {
     const int npieces = (csz * M + 7) / 8;                  // per thread: chunk groups of 8 x 8 token groups over 8 waves
     uint4 xw[NX];
@@ -271,7 +274,13 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
           const int tk = it * 8 + (lane >> 3), c8 = lane & 7;
           const uint4 v = *(const uint4*)(ep + (size_t)tk * kResEpPitch + c8 * 16);
           const int64_t tok = t0 + j * 32 + tk;
-          if (tok < a.T) *(uint4*)(Yh + tok * a.ldy + rb * 64 + c8 * 8) = v;
+          // Y is written once and not read again here: a non-temporal store keeps it from displacing
+          // X and the weight operands in the caches
+          if (tok < a.T) {
+            typedef unsigned rs_u4 __attribute__((ext_vector_type(4)));
+            const rs_u4 vv = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(vv, (rs_u4*)(Yh + tok * a.ldy + rb * 64 + c8 * 8));
+          }
         }
       }
       return;
@@ -295,11 +304,11 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
               if (a.y_fp32) {
                 rs_f4 pk = {acc[t][j][4 * jq] + bv[0], acc[t][j][4 * jq + 1] + bv[1], acc[t][j][4 * jq + 2] + bv[2],
                             acc[t][j][4 * jq + 3] + bv[3]};
-                *(rs_f4*)((float*)a.Y + tok * a.ldy + o) = pk;
+                __builtin_nontemporal_store(pk, (rs_f4*)((float*)a.Y + tok * a.ldy + o));
               } else {
                 rs_h4 pk = {(_Float16)(acc[t][j][4 * jq] + bv[0]), (_Float16)(acc[t][j][4 * jq + 1] + bv[1]),
                             (_Float16)(acc[t][j][4 * jq + 2] + bv[2]), (_Float16)(acc[t][j][4 * jq + 3] + bv[3])};
-                *(rs_h4*)((_Float16*)a.Y + tok * a.ldy + o) = pk;
+                __builtin_nontemporal_store(pk, (rs_h4*)((_Float16*)a.Y + tok * a.ldy + o));
               }
             }
           }
@@ -357,8 +366,9 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
       if constexpr (CHUNKED) {
         // the next image goes into the other buffer (whose last readers passed the previous
         // barrier), the one after it starts travelling
-        if (img + 1 < nimg) x_park(xn, img + 1, 0, (unsigned)((img + 1) & 1) * a.buf_bytes);
-        if (img + 2 < nimg) x_load(xn, img + 2, 0);
+        const int c1 = c + 1 == nchunks ? 0 : c + 1, c2 = c1 + 1 == nchunks ? 0 : c1 + 1;   // chunks of the next two images
+        if (img + 1 < nimg) x_park(xn, c1, 0, (unsigned)((img + 1) & 1) * a.buf_bytes);
+        if (img + 2 < nimg) x_load(xn, c2, 0);
         __syncthreads();
         ++img;
       }

@@ -152,6 +152,9 @@ __global__ void __launch_bounds__(64 * kResWaves) spmm_resident_kernel(const Res
       const unsigned col = col_first + (unsigned)((first + n) * 64);
       xw[n] = *(const uint4*)(x_row + (col < col_last ? col : col_last));
     }
+    // the loads that follow in the program (weight operands) must follow in the instruction stream
+    // too -- loads return in order, and X is what is waited for first
+    __builtin_amdgcn_sched_barrier(0);
   };
   auto x_park = [&](const uint4 (&xw)[NX], int c, int first, unsigned buf) {
     const int64_t col0 = (int64_t)c * csz * 8 * M;

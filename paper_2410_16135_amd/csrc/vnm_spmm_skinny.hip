@@ -278,25 +278,31 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
     const int c_lo = lane & 15, rsub = lane >> 4;
     constexpr int NB = DUAL ? 2 : 1;                 // one batch where the registers allow it
     constexpr int HB = kSkNXR / NB;
+    // All blocks of a thread lie in one token row ((wave + 8 k) & 3 = wave & 3), 256 columns apart:
+    // one row pointer (a valid row also for tokens beyond T) and a 32-bit column, clamped to the last
+    // 8 columns that exist in the K range and in the row -- what a clamped load brings is dropped below.
+    const int x_tok = (wave & 3) * 4 + rsub;
+    const unsigned short* x_row = a.X + (x_tok < a.T ? x_tok * a.ldx : 0);
+    const int64_t span_end = col0 + ncol;
+    const unsigned col_last = (unsigned)((span_end < a.in ? span_end : a.in) - 8);
+    const unsigned col_first = (unsigned)col0 + (unsigned)(((wave >> 2) * 16 + c_lo) * 8);
 #pragma unroll
     for (int half = 0; half < NB; ++half) {
       uint4 xw[HB];
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const int b = wave + kSkWaves * (half * HB + i);
-        const int tok = (b & 3) * 4 + rsub, ch = (b >> 2) * 16 + c_lo;
-        const bool ok = ch < CH && tok < a.T && col0 + ch * 8 < a.in;
-        const unsigned short* src = ok ? a.X + tok * a.ldx + col0 + ch * 8 : a.X;
-        xw[i] = *(const uint4*)src;
+        const unsigned col = col_first + (unsigned)((half * HB + i) * 256);
+        xw[i] = *(const uint4*)(x_row + (col < col_last ? col : col_last));
       }
+      // keep the compiler from moving the weight loads below in front of these: loads return in order
+      __builtin_amdgcn_sched_barrier(0);
       if (half == 0) {
 #pragma unroll
         for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const int b = wave + kSkWaves * (half * HB + i);
-        const int tok = (b & 3) * 4 + rsub, ch = (b >> 2) * 16 + c_lo;
+        const int tok = x_tok, ch = ((wave >> 2) + 2 * (half * HB + i)) * 16 + c_lo;
         if (ch < CH) {
           const bool ok = tok < a.T && col0 + ch * 8 < a.in;
           const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);

@@ -333,9 +333,13 @@ def test_deit_shaped_layers_full(cfg):
         W, X = syn.layer_tensors(layer)
         c = vnm.vnm_prune_compress(_dev(W), layer.V, layer.M, want_mask=True)
         Y = vnm.vnm_spmm(_dev(X), c, path=vnm.PATH_SMFMAC)
+        Wd = vnm.vnm_decompress(c)
         torch.cuda.synchronize()
         _, _, _, mask = _check_compressed(c, W, layer.V, layer.M)
-        Y_ref = orc.matmul_ref(X, orc.masked_dense(W, mask))
+        Wm = orc.masked_dense(W, mask)
+        # (small matrices: pruning and decompression run with spans of one or two K steps here)
+        assert np.array_equal(Wd.cpu().numpy().view(np.uint16), Wm.view(np.uint16)), layer.name
+        Y_ref = orc.matmul_ref(X, Wm)
         err = orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref)
         assert err <= TOL, (layer.name, err)
 

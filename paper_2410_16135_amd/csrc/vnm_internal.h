@@ -130,6 +130,12 @@ int64_t skinny_max_tokens();
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
                        const Fused& f, hipStream_t st);
+// Product for at most gemv_max_tokens() tokens on the vector ALUs (vnm_spmm_gemv.hip): the packed weight
+// streamed once, no matrix instructions, no workspace.  X as for the few-token kernels.
+int64_t gemv_max_tokens();
+bool spmm_gemv_applicable(int64_t T, int64_t ldx, const Dims& d);
+int launch_spmm_gemv(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
+                     void* Y, int64_t ldy, int y_dtype, const Fused& f, hipStream_t st);
 // Single-kernel product without a staging pass (vnm_spmm_resident.hip): the workgroup's slice of X
 // is turned around into LDS by the kernel itself; for a K range that fits LDS, or few enough
 // output channels for K to stream through LDS in chunks.

@@ -443,6 +443,8 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
                        const Fused& f, hipStream_t st) {
+  // one to four tokens: the vector-ALU stream of vnm_spmm_gemv.hip
+  if (spmm_gemv_applicable(T, ldx, d)) return launch_spmm_gemv(X, T, ldx, packed, d, Y, ldy, y_dtype, f, st);
   const PackedLayout pl = packed_layout(d);
   const char* p = (const char*)packed;
   const bool dual = packed_tables(d.V) == 2;

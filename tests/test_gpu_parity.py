@@ -270,6 +270,57 @@ def test_spmm_up_to_16_tokens_x_resident_in_lds(out, inn, T, V, M, ydt):
     assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
 
 
+VECTOR_ALU_CASES = [
+    # out, in, T, V, M: one to four tokens -- the product on the vector ALUs (no matrix instructions): every token
+    # count, one and two column tables (V = 32), 128-row blocks, M from 4 to 16, `in` ragged against M, `out`
+    # ragged against the 32-row tile, a single K step, fewer K steps than waves, more K steps than one ring of
+    # weights per wave (two rounds of loads), rows of X longer than one 16-byte piece per thread
+    (4096, 4096, 1, 64, 5), (4096, 4096, 2, 64, 5), (4096, 4096, 3, 64, 5), (4096, 4096, 4, 64, 5),
+    (2080, 2048, 3, 32, 5), (1000, 4104, 4, 128, 8), (70, 40, 1, 64, 5), (33, 8, 2, 32, 4), (640, 20480, 1, 64, 5),
+    (1024, 11008, 4, 64, 5), (300, 16384, 2, 32, 16), (257, 2048, 4, 64, 7), (96, 1280, 3, 64, 16),
+    # more 32-row tiles than compute units (workgroups of 8 waves); a long K on few tiles at one token
+    (8320, 1288, 3, 64, 5), (11008, 4096, 1, 64, 5), (512, 11008, 1, 128, 5),
+]
+
+
+@pytest.mark.parametrize("out,inn,T,V,M", VECTOR_ALU_CASES)
+@pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
+def test_spmm_up_to_4_tokens_on_the_vector_alus(out, inn, T, V, M, ydt):
+    """The kernel for one to four tokens (the packed weight streamed through the vector ALUs), against the
+    oracle; with integer-valued operands exact, and bit for bit equal to the general kernel."""
+    rng = np.random.default_rng(out + inn + T)
+    W = _rand_w(rng, out, inn, "normal")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(_dev(X), c, out_dtype=ydt, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
+    assert orc.max_normalised_error(Y.float().cpu().numpy(), Y_ref) <= TOL
+    Wi, Xi = syn.small_integer_case(out, inn, T, seed=T + M, lo=-2, hi=2)
+    ci = vnm.vnm_prune_compress(_dev(Wi), V, M, want_mask=True)
+    Ya = vnm.vnm_spmm(_dev(Xi), ci, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+    Yb = vnm.vnm_spmm(_dev(Xi), ci, out_dtype=torch.float32, path=vnm.PATH_GENERIC)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)
+    Yi_ref = orc.matmul_ref(Xi, orc.masked_dense(Wi, ci.mask.cpu().numpy()))
+    assert np.array_equal(Ya.cpu().numpy().astype(np.float64), Yi_ref)
+
+
+def test_spmm_up_to_4_tokens_ignores_what_lies_behind_x():
+    """Rows of X beyond T and the columns between `in` and the row pitch hold NaN: none of it may reach Y."""
+    out, inn, T, V, M = 320, 1288, 3, 64, 5
+    rng = np.random.default_rng(5)
+    W = _rand_w(rng, out, inn, "normal")
+    X = rng.standard_normal((T, inn)).astype(np.float16)
+    big = torch.full((T + 5, inn + 24), float("nan"), dtype=torch.float16, device=DEV)
+    big[:T, :inn] = _dev(X)
+    c = vnm.vnm_prune_compress(_dev(W), V, M, want_mask=True)
+    Y = vnm.vnm_spmm(big[:T, :inn], c, out_dtype=torch.float32, path=vnm.PATH_SMFMAC)
+    torch.cuda.synchronize()
+    Y_ref = orc.matmul_ref(X, orc.masked_dense(W, c.mask.cpu().numpy()))
+    assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
+
+
 def _random_few_token_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []

@@ -641,7 +641,10 @@ def main():
         # few tokens: the product is a stream of the packed weight, bound by HBM, not by the matrix cores
         packed_bytes = float(sum(c.packed.numel() for (_, _, _, c, _, _) in state))
         result["roofline"] = {
-            "bound": "hbm", "kernel": "spmm_skinny_kernel / spmm_skinny_resident_kernel (+ splitk_reduce_kernel)",
+            "bound": "hbm",
+            "kernel": ("spmm_gemv_kernel (vector ALUs; three and four tokens on 4096 x 11008: the matrix-core few-token kernel)"
+                       if L0.tokens <= 4 else
+                       "spmm_skinny_kernel / spmm_skinny_resident_kernel (+ splitk_reduce_kernel)"),
             "achieved": packed_bytes / product_in_step_ms / 1e6, "peak": 8000.0, "unit": "GB/s",
             "frac": packed_bytes / product_in_step_ms / 1e6 / 8000.0, "traffic": None,
             "launches_per_step": len(layers), "avg_launch_us": product_in_step_ms / len(layers) * 1e3,
@@ -679,6 +682,9 @@ def main():
         t_ps = timed(lambda: vnm.vnm_prune_compress_scored(Wd, S, L.V, L.M, out=cs))
         t_16 = timed(lambda: vnm.vnm_spmm(X16, c, Y=Y16), n=30)
         t_16d = timed(lambda: torch.matmul(X16, Wd.t(), out=Y16), n=30)
+        X1, Y1 = Xd[:1].contiguous(), torch.empty((1, L.out), dtype=torch.float16, device=dev)
+        t_1 = timed(lambda: vnm.vnm_spmm(X1, c, Y=Y1), n=30)
+        t_1d = timed(lambda: torch.matmul(X1, Wd.t(), out=Y1), n=30)
         # fused layer of Section 4.2, Eq. 6: bias and run-time channel permutations around the product
         g = torch.Generator(device="cpu").manual_seed(7)
         p_in = torch.randperm(L.inn, generator=g).to(torch.int32).to(dev)
@@ -746,6 +752,7 @@ def main():
             "ria_scores_gbps": (2 * w_bytes + 2 * w_bytes) / t_ria / 1e6,
             "prune_compress_scored_gbps": (w_bytes + 2 * w_bytes) / t_ps / 1e6,
             "spmm_16_tokens_ms": t_16, "dense_16_tokens_ms": t_16d,
+            "spmm_1_token_ms": t_1, "dense_1_token_ms": t_1d,
             "note": "HIP-event means including launch gaps; bytes counted: RIA reads W twice and writes fp32 "
                     "scores; scored pruning reads W and the scores"}
     if args.sclk:

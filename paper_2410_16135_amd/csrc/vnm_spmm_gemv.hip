@@ -241,10 +241,11 @@ bool spmm_gemv_applicable(int64_t T, int64_t ldx, const Dims& d) {
   // 32-bit byte offsets: rows of X, the packed copy, raw column numbers
   if (T * ldx * 2 > 0x7FFFFFFF || packed_layout(d).total > 0x7FFFFFFF || d.S * 8 * d.M + 128 > 0x7FFFFFFF) return false;
   if (2 * packed_row_blocks(d) > 0x7FFFFFFF) return false;
-  // Three and four tokens on few tiles with a long K: the vector ALUs of the (at most 256) busy units
-  // become the limit and the matrix-core kernel with K split over workgroups is faster (4096 x 11008,
-  // 276 K steps, four tokens: 16.4 against 15.5 us; 4096 x 4096, 103 steps: 8.0 against 11.7 us)
-  if (T > 2 && 2 * packed_row_blocks(d) <= 256 && d.S > 224) return false;
+  // Three and four tokens: only where the tiles leave compute units idle and K is short.  Otherwise the
+  // vector ALUs become the limit and the matrix-core few-token kernel is faster (device time per call
+  // at four tokens, 64:2:5, weights from HBM, this kernel / that one: 4096 x 4096, 103 K steps, 8.0 / 10.6 us;
+  // 11008 x 4096, 344 tiles, 13.2 / 12.7 us; 4096 x 11008, 276 K steps, 16.4 / 13.8 us)
+  if (T > 2 && (2 * packed_row_blocks(d) > 256 || d.S > 224)) return false;
   return gemv_lds(gemv_ntok(T), d.in, gemv_waves(d), kGvRing) <= 150 * 1024;
 }
 

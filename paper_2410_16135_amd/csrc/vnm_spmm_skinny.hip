@@ -239,9 +239,12 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
   constexpr int AT = 2, TT = 16;
   constexpr int NT = HALF ? 1 : AT;                  // tiles of this workgroup
   const int t0 = HALF ? (int)blockIdx.z : 0;         // its first tile
-  // 8 operands ahead: 10 fit without spilling and measured no faster; 13 of one tile's (half as large,
-  // all steps of a wave at 104 K steps) measured slower from HBM (18.0 against 15.9 us on 4096 x 4096)
-  constexpr int kSkRing = 8;
+  // 4 operands ahead.  Deeper rings are slower, not faster: what keeps the stream going is the number of
+  // waves on the unit, and every further operand in flight is another load instruction queued in front
+  // of the ones a wave waits for.  Device time per call at 16 tokens, 64:2:5, weights from HBM, ring
+  // 8 / 4 / 2: 4096 x 4096 12.2 / 10.9 / 12.2 us, 11008 x 4096 14.7 / 13.2 / 12.9 us, 4096 x 11008
+  // 17.2 / 14.4 / 14.3 us (10 and 13 had measured no better than 8 before).
+  constexpr int kSkRing = 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -42,7 +42,7 @@ FUSED_CASES = [
     (8256, 1320, 12, 64, 5), (4096, 5600, 16, 64, 5),
     # one to four tokens, the product on the vector ALUs: 16 waves per tile, 8 waves (more tiles than compute
     # units), two column tables
-    (1024, 1280, 1, 64, 5), (8320, 1320, 3, 64, 5), (352, 2048, 4, 32, 8),
+    (1024, 1280, 1, 64, 5), (8320, 1320, 2, 64, 5), (352, 2048, 4, 32, 8),
 ]
 WHICH = [("bias",), ("perm_in",), ("perm_out",), ("bias", "perm_in", "perm_out")]
 

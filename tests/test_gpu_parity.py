@@ -278,8 +278,9 @@ VECTOR_ALU_CASES = [
     (4096, 4096, 1, 64, 5), (4096, 4096, 2, 64, 5), (4096, 4096, 3, 64, 5), (4096, 4096, 4, 64, 5),
     (2080, 2048, 3, 32, 5), (1000, 4104, 4, 128, 8), (70, 40, 1, 64, 5), (33, 8, 2, 32, 4), (640, 20480, 1, 64, 5),
     (1024, 11008, 4, 64, 5), (300, 16384, 2, 32, 16), (257, 2048, 4, 64, 7), (96, 1280, 3, 64, 16),
-    # more 32-row tiles than compute units (workgroups of 8 waves); a long K on few tiles at one token
-    (8320, 1288, 3, 64, 5), (11008, 4096, 1, 64, 5), (512, 11008, 1, 128, 5),
+    # more 32-row tiles than compute units (workgroups of 8 waves; with three tokens the matrix-core kernel
+    # takes over); a long K on few tiles at one token
+    (8320, 1288, 2, 64, 5), (8320, 1288, 3, 64, 5), (11008, 4096, 1, 64, 5), (512, 11008, 1, 128, 5),
 ]
 
 

@@ -13,7 +13,7 @@
 // (conflict-free: lanes differ in the row).  That is 16 LDS instructions per matrix instruction
 // pair, far below what the streaming rate needs; the transposing staged layout of the many-token
 // kernel would cost a second launch.  For at most 16 tokens a second kernel (further down) keeps the
-// whole slice of X in LDS and uses the registers for a deeper weight stream instead.
+// whole slice of X in LDS and runs 16 waves with a short ring of weight operands each instead.
 //
 // Measured and dropped: dealing the (row block, K step) pairs out evenly to one workgroup per compute
 // unit and adding the parts up inside the kernel (parts to memory with device-scope stores, one arrival
@@ -224,27 +224,30 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_kernel(const Skinny
 
 // Up to 16 tokens whose slice of X fits LDS as a whole (16 rows of the workgroup's K range: in <= ~4800
 // columns unsplit, more with split K): X is fetched once, up front, and then nothing is written to LDS
-// any more, so the K loop needs no barrier and no registers for X.  The registers go to the weight
-// stream instead: every wave keeps 8 to 10 A operands (steps wave, wave + 8, ...) requested ahead of the
-// one it multiplies -- twice the bytes in flight of the phased kernel above, which is what a stream
-// that is bound by memory round trips, not by bytes, needs.  All loads are unconditional (clamped to
-// the last step), so the compiler can wait for exactly the operand it uses next.
-constexpr int kSkNXR = 18;       // 16-byte pieces of X per thread, at most (16 rows of at most 9216 bytes)
+// any more, so the K loop needs no barrier and no registers for X.  A workgroup has 16 waves; every wave
+// takes the steps wave, wave + 16, ... and keeps a short ring of A operands requested ahead of the one it
+// multiplies.  All loads are unconditional (clamped to the last step), so the compiler can wait for
+// exactly the operand it uses next.  What keeps the weight stream going is the number of waves on the
+// compute unit, not the depth of a wave's ring: device time per call at 16 tokens, 64:2:5, weights from
+// HBM, on 4096 x 4096 / 11008 x 4096 / 4096 x 11008 --
+//   8 waves, ring 8:  12.2 / 14.7 / 17.2 us      8 waves, ring 4:  10.9 / 13.2 / 14.4 us
+//   16 waves, ring 4: 10.6 / 13.7 / 14.7 us      16 waves, ring 3: 10.1 / 13.4 / 14.9 us
+//   16 waves, ring 2:  9.6 / 13.0 / 14.2 us      16 waves, ring 1:  9.5 / 12.5 / 14.2 us
+// (rings of 10 and 13 had measured no better than 8 before).  Every further operand in flight is another
+// load instruction queued in the unit's memory pipeline in front of the ones some wave is waiting for.
+constexpr int kSkWavesR = 16;    // waves per workgroup of the resident-X kernel
+constexpr int kSkNXR = 10;       // 16-byte pieces of X per thread, at most (16 rows of at most 9216 bytes)
 
 // HALF: one workgroup per 32-row tile (blockIdx.z picks the tile of the 64-row block) instead of one per
 // block -- twice the workgroups where a matrix has too few row blocks to occupy the compute units; each
 // fetches the whole slice of X but only its tile's weights.
 template <bool DUAL, bool HALF>
-__global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(const SkinnyArgs a) {
+__global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(const SkinnyArgs a) {
   constexpr int AT = 2, TT = 16;
   constexpr int NT = HALF ? 1 : AT;                  // tiles of this workgroup
   const int t0 = HALF ? (int)blockIdx.z : 0;         // its first tile
-  // 4 operands ahead.  Deeper rings are slower, not faster: what keeps the stream going is the number of
-  // waves on the unit, and every further operand in flight is another load instruction queued in front
-  // of the ones a wave waits for.  Device time per call at 16 tokens, 64:2:5, weights from HBM, ring
-  // 8 / 4 / 2: 4096 x 4096 12.2 / 10.9 / 12.2 us, 11008 x 4096 14.7 / 13.2 / 12.9 us, 4096 x 11008
-  // 17.2 / 14.4 / 14.3 us (10 and 13 had measured no better than 8 before).
-  constexpr int kSkRing = 4;
+  // operands requested ahead per wave (see the table above)
+  constexpr int kSkRing = 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -272,7 +275,7 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
 
   // X slice -> LDS, [token][raw column], in 16-byte pieces.  One wave-wide load takes a block of 4 token
   // rows x 16 chunks (256-byte runs of a row: whole cache lines; in LDS the four rows start an odd number
-  // of dwords apart, so the 64 lanes' stores fall into 64 different banks); block number wave + 8 i is
+  // of dwords apart, so the 64 lanes' stores fall into 64 different banks); block number wave + 16 i is
   // (token group b & 3, chunk group b >> 2).  Rows beyond T and columns beyond `in` become zero.  The
   // first ring of weight operands is requested right after X: loads return in order, so X (from L2) is
   // not held up behind the weights (from HBM), and the weights travel while X is being parked in LDS.
@@ -281,7 +284,7 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
     const int c_lo = lane & 15, rsub = lane >> 4;
     constexpr int NB = DUAL ? 2 : 1;                 // one batch where the registers allow it
     constexpr int HB = kSkNXR / NB;
-    // All blocks of a thread lie in one token row ((wave + 8 k) & 3 = wave & 3), 256 columns apart:
+    // All blocks of a thread lie in one token row ((wave + 16 k) & 3 = wave & 3), 512 columns apart:
     // one row pointer (a valid row also for tokens beyond T) and a 32-bit column, clamped to the last
     // 8 columns that exist in the K range and in the row -- what a clamped load brings is dropped below.
     const int x_tok = (wave & 3) * 4 + rsub;
@@ -289,23 +292,24 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
     const int64_t span_end = col0 + ncol;
     const unsigned col_last = (unsigned)((span_end < a.in ? span_end : a.in) - 8);
     const unsigned col_first = (unsigned)col0 + (unsigned)(((wave >> 2) * 16 + c_lo) * 8);
+    constexpr int CG = kSkWavesR / 4;               // chunk groups of 16 pieces taken per round of wave-wide loads
 #pragma unroll
     for (int half = 0; half < NB; ++half) {
       uint4 xw[HB];
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const unsigned col = col_first + (unsigned)((half * HB + i) * 256);
+        const unsigned col = col_first + (unsigned)((half * HB + i) * (CG * 128));
         xw[i] = *(const uint4*)(x_row + (col < col_last ? col : col_last));
       }
       // keep the compiler from moving the weight loads below in front of these: loads return in order
       __builtin_amdgcn_sched_barrier(0);
       if (half == 0) {
 #pragma unroll
-        for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWaves * i);
+        for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWavesR * i);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const int tok = x_tok, ch = ((wave >> 2) + 2 * (half * HB + i)) * 16 + c_lo;
+        const int tok = x_tok, ch = ((wave >> 2) + CG * (half * HB + i)) * 16 + c_lo;
         if (ch < CH) {
           const bool ok = tok < a.T && col0 + ch * 8 < a.in;
           const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);
@@ -370,12 +374,12 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
     }
   };
 
-  for (int64_t sb = s_lo + wave; sb < s_hi; sb += kSkWaves * kSkRing) {
+  for (int64_t sb = s_lo + wave; sb < s_hi; sb += kSkWavesR * kSkRing) {
 #pragma unroll
     for (int i = 0; i < kSkRing; ++i) {
-      const int64_t s = sb + kSkWaves * i;
+      const int64_t s = sb + kSkWavesR * i;
       if (s < s_hi) compute(ring[i], s);
-      load_a(ring[i], s + kSkWaves * kSkRing);
+      load_a(ring[i], s + kSkWavesR * kSkRing);
     }
   }
   __syncthreads();                                   // every wave is done with X: the reduction reuses its LDS
@@ -391,13 +395,13 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
       for (int j = 0; j < 16; ++j) mine[t * 32 + 8 * (j >> 2) + 4 * hB + (j & 3)] = acc[t][j];
   }
   __syncthreads();
-  for (int e = tid; e < TT * RT; e += 64 * kSkWaves) {
+  for (int e = tid; e < TT * RT; e += 64 * kSkWavesR) {
     const int tok = e / RT, rw = e - tok * RT;
     const int64_t o = r * RW + t0 * 32 + rw;
     if (tok < a.T && o < a.out) {
       float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < kSkWaves; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
+      for (int w = 0; w < kSkWavesR; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
       if (a.bias) sum += (float)a.bias[o];
       const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
       if (dst < 0 || dst >= a.out) continue;
@@ -410,10 +414,10 @@ __global__ void __launch_bounds__(64 * kSkWaves) spmm_skinny_resident_kernel(con
 // LDS of the resident-X kernel for nsz K steps per workgroup; 0 if they do not fit
 static size_t skinny_resident_lds(int M, int64_t nsz) {
   const size_t x = (size_t)16 * ((size_t)nsz * 16 * M + 4);
-  const size_t red = (size_t)kSkWaves * 16 * (2 * 32 + 1) * 4;
+  const size_t red = (size_t)kSkWavesR * 16 * (2 * 32 + 1) * 4;
   const size_t lds = x > red ? x : red;
   // kSkNXR wave-wide loads per wave cover the slice: 4 token groups x ceil(nsz M / 16) chunk groups
-  if (lds > 150 * 1024 || 4 * (((size_t)nsz * M + 15) / 16) > (size_t)kSkWaves * kSkNXR) return 0;
+  if (lds > 150 * 1024 || 4 * (((size_t)nsz * M + 15) / 16) > (size_t)kSkWavesR * kSkNXR) return 0;
   return lds;
 }
 
@@ -421,7 +425,7 @@ template <bool DUAL, bool HALF>
 static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
   auto kern = spmm_skinny_resident_kernel<DUAL, HALF>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
-  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS, HALF ? 2u : 1u), dim3(64 * kSkWaves), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS, HALF ? 2u : 1u), dim3(64 * kSkWavesR), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;

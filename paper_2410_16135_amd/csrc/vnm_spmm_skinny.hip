@@ -57,6 +57,7 @@ struct SkinnyArgs {
   // partial product at Y + z * z_stride elements (a scratch then; summed by splitk_reduce)
   int npz; int64_t z_stride;
   int nsz;                       // resident-X kernel: K steps per workgroup (split K as above, counted in steps)
+  int tgroups;                   // resident-X kernel: groups of 16 tokens, one workgroup each per (row block, K piece)
   // fused epilogue (null = none): bias per weight row, destination channel per weight row
   const _Float16* bias; const int* perm_out;
 };
@@ -254,7 +255,12 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
   const int64_t r = blockIdx.x;
   const int M = a.M;
   const int64_t S = a.S;
-  const int64_t s_lo = (int64_t)blockIdx.y * a.nsz;
+  // blockIdx.y = K piece * token groups + token group; a group is 16 token rows of X and Y
+  const int tg = (int)(blockIdx.y % (unsigned)a.tgroups);
+  const int64_t ky = blockIdx.y / (unsigned)a.tgroups;
+  const int64_t Tg = a.T - 16 * tg < 16 ? a.T - 16 * tg : 16;       // tokens of this group (at least one)
+  const unsigned short* Xg = a.X + (int64_t)tg * 16 * a.ldx;
+  const int64_t s_lo = ky * a.nsz;
   const int64_t s_hi = s_lo + a.nsz < S ? s_lo + a.nsz : S;
   const int ncol = a.nsz * 8 * M;                    // raw columns of a workgroup's K range
   const int pitch = ncol * 2 + 4;                    // bytes per token row: odd number of dwords
@@ -288,7 +294,7 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
     // one row pointer (a valid row also for tokens beyond T) and a 32-bit column, clamped to the last
     // 8 columns that exist in the K range and in the row -- what a clamped load brings is dropped below.
     const int x_tok = (wave & 3) * 4 + rsub;
-    const unsigned short* x_row = a.X + (x_tok < a.T ? x_tok * a.ldx : 0);
+    const unsigned short* x_row = Xg + (x_tok < Tg ? x_tok * a.ldx : 0);
     const int64_t span_end = col0 + ncol;
     const unsigned col_last = (unsigned)((span_end < a.in ? span_end : a.in) - 8);
     const unsigned col_first = (unsigned)col0 + (unsigned)(((wave >> 2) * 16 + c_lo) * 8);
@@ -311,7 +317,7 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
       for (int i = 0; i < HB; ++i) {
         const int tok = x_tok, ch = ((wave >> 2) + CG * (half * HB + i)) * 16 + c_lo;
         if (ch < CH) {
-          const bool ok = tok < a.T && col0 + ch * 8 < a.in;
+          const bool ok = tok < Tg && col0 + ch * 8 < a.in;
           const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);
           unsigned* d = (unsigned*)(smem + (size_t)tok * pitch + ch * 16);
           d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
@@ -398,15 +404,16 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
   for (int e = tid; e < TT * RT; e += 64 * kSkWavesR) {
     const int tok = e / RT, rw = e - tok * RT;
     const int64_t o = r * RW + t0 * 32 + rw;
-    if (tok < a.T && o < a.out) {
+    if (tok < Tg && o < a.out) {
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < kSkWavesR; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
       if (a.bias) sum += (float)a.bias[o];
       const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
       if (dst < 0 || dst >= a.out) continue;
-      if (a.y_fp32) ((float*)a.Y)[(int64_t)blockIdx.y * a.z_stride + tok * a.ldy + dst] = sum;
-      else ((_Float16*)a.Y)[tok * a.ldy + dst] = (_Float16)sum;
+      const int64_t yrow = 16 * tg + tok;
+      if (a.y_fp32) ((float*)a.Y)[ky * a.z_stride + yrow * a.ldy + dst] = sum;
+      else ((_Float16*)a.Y)[yrow * a.ldy + dst] = (_Float16)sum;
     }
   }
 }
@@ -425,7 +432,7 @@ template <bool DUAL, bool HALF>
 static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
   auto kern = spmm_skinny_resident_kernel<DUAL, HALF>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
-  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)KS, HALF ? 2u : 1u), dim3(64 * kSkWavesR), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)(KS * a.tgroups), HALF ? 2u : 1u), dim3(64 * kSkWavesR), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
@@ -466,15 +473,19 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
-  if (T <= 16) {
+  // 17 to 32 tokens as two groups of 16 of the resident-X kernel where the two workgroups per row block
+  // still fit the compute units at once (4096-row layers: the packed weight is then read twice, from
+  // HBM once; device time per call at 64:2:5, 4096 x 4096: 10 us against 14 us for the phased kernel)
+  const int groups = T <= 16 ? 1 : 2;
+  if (T <= 16 || R * groups <= 128) {
     // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
     // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
     // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
     // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
     // in four against 18.1 us split in two)
     int64_t ks = 1;
-    if (scratch && R <= 128 && d.S > 128) {
-      ks = 256 / R;
+    if (scratch && R * groups <= 128 && d.S > 128) {
+      ks = 256 / (R * groups);
       if (ks > 16) ks = 16;
       if (ks > d.S / 32) ks = d.S / 32;
       while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
@@ -484,13 +495,13 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
     // below 32 steps per workgroup (4 per wave) there is nothing to keep in flight: the phased kernel
     const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz) : 0;
     if (lds) {
-      a.nsz = (int)nsz; a.z_stride = 0;
+      a.nsz = (int)nsz; a.z_stride = 0; a.tgroups = groups;
       if (KSr > 1) {
         a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
         a.bias = nullptr; a.perm_out = nullptr;                           // applied by the reduction
       }
       // one workgroup per 32-row tile while even those leave compute units idle
-      const bool half = 2 * R * KSr <= kSkHalfTileMaxWorkgroups;
+      const bool half = 2 * R * KSr * groups <= kSkHalfTileMaxWorkgroups;
       const int rc = dual ? (half ? launch_skinny_resident<true, true>(a, R, KSr, lds, st) : launch_skinny_resident<true, false>(a, R, KSr, lds, st))
                           : (half ? launch_skinny_resident<false, true>(a, R, KSr, lds, st) : launch_skinny_resident<false, false>(a, R, KSr, lds, st));
       if (rc != VNM_OK || KSr == 1) return rc;

@@ -244,14 +244,19 @@ RESIDENT_X_CASES = [
     # at most 128 row blocks, K unsplit: one workgroup per 32-row tile -- one column table, two tables (V = 32),
     # 128-row blocks, and V = 32 with an odd number of 32-row blocks (the last 64-row block has one real tile)
     (4096, 4096, 16, 64, 5), (4096, 2080, 9, 32, 6), (2048, 4104, 13, 128, 8), (2080, 2048, 7, 32, 5),
+    # 17 to 32 tokens on at most 64 row blocks: the same kernel, two groups of 16 tokens per row block (a full and
+    # a ragged second group, two column tables, 128-row blocks, and K split over workgroups as well)
+    (4096, 4096, 32, 64, 5), (4096, 2080, 17, 32, 6), (2048, 4104, 25, 128, 8), (2080, 2048, 31, 32, 5),
+    (1024, 11008, 20, 64, 5),
 ]
 
 
 @pytest.mark.parametrize("out,inn,T,V,M", RESIDENT_X_CASES)
 @pytest.mark.parametrize("ydt", [torch.float16, torch.float32])
 def test_spmm_up_to_16_tokens_x_resident_in_lds(out, inn, T, V, M, ydt):
-    """The few-token kernel with X resident in LDS and a ring of weight operands in flight, against the
-    oracle; with integer-valued operands bit for bit against the general kernel."""
+    """The few-token kernel with X resident in LDS and a ring of weight operands in flight (up to 16 tokens per
+    workgroup, up to 32 per call), against the oracle; with integer-valued operands bit for bit against the
+    general kernel."""
     rng = np.random.default_rng(out + inn + T)
     W = _rand_w(rng, out, inn, "normal")
     X = rng.standard_normal((T, inn)).astype(np.float16)

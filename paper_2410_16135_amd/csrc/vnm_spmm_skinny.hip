@@ -454,6 +454,13 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
   return VNM_OK;
 }
 
+// 33 to 64 tokens on few row blocks: groups of 16 tokens of the resident-X kernel, K unsplit (see the launcher)
+bool skinny_groups_applicable(int64_t T, const Dims& d) {
+  if (T <= skinny_max_tokens() || T > 64 || !has_packed(d.V, d.M)) return false;
+  const int64_t groups = (T + 15) / 16;
+  return packed_row_blocks(d) * groups <= kSkHalfTileMaxWorkgroups && d.S >= 32 && skinny_resident_lds(d.M, d.S) > 0;
+}
+
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
                        const Fused& f, hipStream_t st) {
@@ -473,18 +480,20 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
-  // 17 to 32 tokens as two groups of 16 of the resident-X kernel where the two workgroups per row block
-  // still fit the compute units at once (4096-row layers: the packed weight is then read twice, from
-  // HBM once; device time per call at 64:2:5, 4096 x 4096: 10 us against 14 us for the phased kernel)
-  const int groups = T <= 16 ? 1 : 2;
-  if (T <= 16 || R * groups <= 128) {
+  // More than 16 tokens as groups of 16 of the resident-X kernel, one workgroup per (row block, group),
+  // where those workgroups still fit the compute units at once (the 4096-row layers up to 64 tokens: the
+  // packed weight is then requested once per group and comes from HBM once; device time per call at
+  // 64:2:5 on 4096 x 4096 at 32 tokens: 9.7 us against 14.6 us for the phased kernel)
+  const int groups = (int)((T + 15) / 16);
+  if (T > skinny_max_tokens() && !skinny_groups_applicable(T, d)) return VNM_ERR_UNSUPPORTED;
+  if (T <= 16 || R * groups <= kSkHalfTileMaxWorkgroups) {
     // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
     // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
     // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
     // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
     // in four against 18.1 us split in two)
     int64_t ks = 1;
-    if (scratch && R * groups <= 128 && d.S > 128) {
+    if (scratch && T <= skinny_max_tokens() && R * groups <= 128 && d.S > 128) {
       ks = 256 / (R * groups);
       if (ks > 16) ks = 16;
       if (ks > d.S / 32) ks = d.S / 32;
@@ -508,6 +517,7 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
       return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
     }
   }
+  if (T > skinny_max_tokens()) return VNM_ERR_UNSUPPORTED;               // the phased kernel holds at most 32 token rows
   // steps per phase: a multiple of the 8 waves, at most 32, with at most kSkNX pieces of X per thread
   // (TT * P * M <= 512 * kSkNX), which also keeps the two LDS buffers below 132 KiB
   int P = 512 * kSkNX / (TT * d.M) / 8 * 8;

@@ -248,6 +248,8 @@ RESIDENT_X_CASES = [
     # a ragged second group, two column tables, 128-row blocks, and K split over workgroups as well)
     (4096, 4096, 32, 64, 5), (4096, 2080, 17, 32, 6), (2048, 4104, 25, 128, 8), (2080, 2048, 31, 32, 5),
     (1024, 11008, 20, 64, 5),
+    # 33 to 64 tokens while (row blocks x groups of 16 tokens) still fit the compute units at once
+    (4096, 4096, 33, 64, 5), (4096, 4096, 64, 64, 5), (2080, 2048, 50, 32, 5), (2048, 4104, 64, 128, 8), (5000, 2048, 40, 64, 8),
 ]
 
 

@@ -266,6 +266,32 @@ def vnm_spmm(X, c: Compressed, N: int = 2, out_dtype=None, path: int = PATH_AUTO
     return Y
 
 
+def vnm_spmm_bind(X, c: Compressed, Y, workspace, N: int = 2, path: int = PATH_AUTO):
+    """The vnm_spmm call on these buffers with its arguments marshalled once: returns a function of
+    no arguments that issues the call on torch's current stream (a loop that serves the same layer
+    again and again -- decoding -- pays the argument conversion once, not per call).  The tensors
+    must stay alive and in place while the function is used."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    T = X.shape[0]
+    assert T > 0 and X.shape[1] == c.inn and Y.shape == (T, c.out) and Y.stride(1) == 1
+    y_dtype = {torch.float16: 0, torch.float32: 1}[Y.dtype]
+    fn = load_library().vnm_spmm
+    args = (_ptr(X), ctypes.c_int64(T), ctypes.c_int64(X.stride(0)), _ptr(c.values), _ptr(c.meta), _ptr(c.colidx),
+            _ptr(c.packed), ctypes.c_int64(c.out), ctypes.c_int64(c.inn), ctypes.c_int(c.V), ctypes.c_int(N),
+            ctypes.c_int(c.M), _ptr(Y), ctypes.c_int64(Y.stride(0)), ctypes.c_int(y_dtype), ctypes.c_int(path),
+            _ptr(workspace), ctypes.c_int64(0 if workspace is None else workspace.numel()))
+    dev = X.device
+    keep = (X, c, Y, workspace)
+
+    def call():
+        rc = fn(*args, torch.cuda.current_stream(dev).cuda_stream)
+        if rc:
+            _check(rc, "vnm_spmm")
+        return keep[2]
+    return call
+
+
 NOALLOC_SCRATCH_BYTES = 32 << 20
 
 

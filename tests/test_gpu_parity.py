@@ -329,6 +329,25 @@ def test_spmm_up_to_4_tokens_ignores_what_lies_behind_x():
     assert orc.max_normalised_error(Y.cpu().numpy(), Y_ref) <= TOL
 
 
+def test_spmm_bound_call_equals_the_plain_call():
+    """vnm_spmm_bind marshals the arguments once; the call it returns must do what vnm_spmm does (few tokens, the
+    single-kernel path for short K, and the staged path), also when called repeatedly."""
+    for (out, inn, T, V, M) in [(1024, 2048, 1, 64, 5), (1024, 2048, 16, 64, 5), (384, 384, 200, 64, 5), (512, 4096, 300, 64, 5)]:
+        rng = np.random.default_rng(out + T)
+        W = _rand_w(rng, out, inn, "normal")
+        X = _dev(rng.standard_normal((T, inn)).astype(np.float16))
+        c = vnm.vnm_prune_compress(_dev(W), V, M)
+        ws = torch.empty(max(vnm.vnm_spmm_workspace_bytes(T, c), 256), dtype=torch.uint8, device=DEV)
+        Y_ref = vnm.vnm_spmm(X, c, workspace=ws)
+        Y = torch.zeros_like(Y_ref)
+        call = vnm.vnm_spmm_bind(X, c, Y, ws)
+        for _ in range(3):
+            Y.zero_()
+            assert call() is Y
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y_ref)
+
+
 def _random_few_token_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []

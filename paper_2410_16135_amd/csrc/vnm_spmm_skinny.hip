@@ -58,6 +58,7 @@ struct SkinnyArgs {
   int npz; int64_t z_stride;
   int nsz;                       // resident-X kernel: K steps per workgroup (split K as above, counted in steps)
   int tgroups;                   // resident-X kernel: groups of 16 tokens, one workgroup each per (row block, K piece)
+  int64_t R;                     // resident-X kernel: 64-row blocks of the packed copy
   // fused epilogue (null = none): bias per weight row, destination channel per weight row
   const _Float16* bias; const int* perm_out;
 };
@@ -242,7 +243,7 @@ constexpr int kSkNXR = 10;       // 16-byte pieces of X per thread, at most (16 
 // HALF: one workgroup per 32-row tile (blockIdx.z picks the tile of the 64-row block) instead of one per
 // block -- twice the workgroups where a matrix has too few row blocks to occupy the compute units; each
 // fetches the whole slice of X but only its tile's weights.
-template <bool DUAL, bool HALF>
+template <bool DUAL, bool HALF, int RB>
 __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(const SkinnyArgs a) {
   constexpr int AT = 2, TT = 16;
   constexpr int NT = HALF ? 1 : AT;                  // tiles of this workgroup
@@ -252,7 +253,12 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t r = blockIdx.x;
+  // RB row blocks per workgroup, kSkWavesR / RB waves each; a row block beyond the last one (odd count) is
+  // computed as a copy of the last and not stored
+  constexpr int WPB = kSkWavesR / RB;
+  const int rbi = wave / WPB, wsub = wave % WPB;
+  const int64_t r_own = (int64_t)blockIdx.x * RB + rbi;
+  const int64_t r = r_own < a.R ? r_own : a.R - 1;
   const int M = a.M;
   const int64_t S = a.S;
   // blockIdx.y = K piece * token groups + token group; a group is 16 token rows of X and Y
@@ -311,7 +317,7 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
       __builtin_amdgcn_sched_barrier(0);
       if (half == 0) {
 #pragma unroll
-        for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wave + kSkWavesR * i);
+        for (int i = 0; i < kSkRing; ++i) load_a(ring[i], s_lo + wsub + WPB * i);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
@@ -380,12 +386,12 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
     }
   };
 
-  for (int64_t sb = s_lo + wave; sb < s_hi; sb += kSkWavesR * kSkRing) {
+  for (int64_t sb = s_lo + wsub; sb < s_hi; sb += WPB * kSkRing) {
 #pragma unroll
     for (int i = 0; i < kSkRing; ++i) {
-      const int64_t s = sb + kSkWavesR * i;
+      const int64_t s = sb + WPB * i;
       if (s < s_hi) compute(ring[i], s);
-      load_a(ring[i], s + kSkWavesR * kSkRing);
+      load_a(ring[i], s + WPB * kSkRing);
     }
   }
   __syncthreads();                                   // every wave is done with X: the reduction reuses its LDS
@@ -401,13 +407,14 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
       for (int j = 0; j < 16; ++j) mine[t * 32 + 8 * (j >> 2) + 4 * hB + (j & 3)] = acc[t][j];
   }
   __syncthreads();
-  for (int e = tid; e < TT * RT; e += 64 * kSkWavesR) {
-    const int tok = e / RT, rw = e - tok * RT;
-    const int64_t o = r * RW + t0 * 32 + rw;
+  for (int e = tid; e < RB * TT * RT; e += 64 * kSkWavesR) {
+    const int rb = e / (TT * RT), e1 = e - rb * (TT * RT);
+    const int tok = e1 / RT, rw = e1 - tok * RT;
+    const int64_t o = ((int64_t)blockIdx.x * RB + rb) * RW + t0 * 32 + rw;
     if (tok < Tg && o < a.out) {
       float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < kSkWavesR; ++w) sum += red[((size_t)w * TT + tok) * (RW + 1) + rw];
+      for (int w = 0; w < WPB; ++w) sum += red[((size_t)(rb * WPB + w) * TT + tok) * (RW + 1) + rw];
       if (a.bias) sum += (float)a.bias[o];
       const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
       if (dst < 0 || dst >= a.out) continue;
@@ -428,11 +435,12 @@ static size_t skinny_resident_lds(int M, int64_t nsz) {
   return lds;
 }
 
-template <bool DUAL, bool HALF>
+template <bool DUAL, bool HALF, int RB>
 static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
-  auto kern = spmm_skinny_resident_kernel<DUAL, HALF>;
+  auto kern = spmm_skinny_resident_kernel<DUAL, HALF, RB>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
-  hipLaunchKernelGGL(kern, dim3((unsigned)R, (unsigned)(KS * a.tgroups), HALF ? 2u : 1u), dim3(64 * kSkWavesR), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)((R + RB - 1) / RB), (unsigned)(KS * a.tgroups), HALF ? 2u : 1u),
+                     dim3(64 * kSkWavesR), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
@@ -458,7 +466,8 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
 bool skinny_groups_applicable(int64_t T, const Dims& d) {
   if (T <= skinny_max_tokens() || T > 64 || !has_packed(d.V, d.M)) return false;
   const int64_t groups = (T + 15) / 16;
-  return packed_row_blocks(d) * groups <= kSkHalfTileMaxWorkgroups && d.S >= 32 && skinny_resident_lds(d.M, d.S) > 0;
+  // one or two row blocks per workgroup (see the launcher), K unsplit
+  return (packed_row_blocks(d) + 1) / 2 * groups <= kSkHalfTileMaxWorkgroups && d.S >= 32 && skinny_resident_lds(d.M, d.S) > 0;
 }
 
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
@@ -486,15 +495,19 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   // 64:2:5 on 4096 x 4096 at 32 tokens: 9.7 us against 14.6 us for the phased kernel)
   const int groups = (int)((T + 15) / 16);
   if (T > skinny_max_tokens() && !skinny_groups_applicable(T, d)) return VNM_ERR_UNSUPPORTED;
-  if (T <= 16 || R * groups <= kSkHalfTileMaxWorkgroups) {
-    // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
-    // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
-    // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
-    // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
-    // in four against 18.1 us split in two)
+  // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
+  // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
+  // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
+  // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
+  // in four against 18.1 us split in two).  With several token groups, a workgroup takes two row blocks
+  // (8 waves each, one slice of X for both) where one per workgroup would not fit the compute units at
+  // once or would need a slice of X larger than LDS.
+  for (int rb = 1; rb <= (groups > 1 ? 2 : 1); ++rb) {
+    const int64_t Re = (R + rb - 1) / rb;                                 // workgroups along the rows
+    if (T > 16 && Re * groups > kSkHalfTileMaxWorkgroups) continue;
     int64_t ks = 1;
-    if (scratch && T <= skinny_max_tokens() && R * groups <= 128 && d.S > 128) {
-      ks = 256 / (R * groups);
+    if (scratch && T <= skinny_max_tokens() && Re * groups <= 128 && d.S > 128) {
+      ks = 256 / (Re * groups);
       if (ks > 16) ks = 16;
       if (ks > d.S / 32) ks = d.S / 32;
       while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
@@ -503,19 +516,20 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
     const int KSr = (int)((d.S + nsz - 1) / nsz);
     // below 32 steps per workgroup (4 per wave) there is nothing to keep in flight: the phased kernel
     const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz) : 0;
-    if (lds) {
-      a.nsz = (int)nsz; a.z_stride = 0; a.tgroups = groups;
-      if (KSr > 1) {
-        a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
-        a.bias = nullptr; a.perm_out = nullptr;                           // applied by the reduction
-      }
-      // one workgroup per 32-row tile while even those leave compute units idle
-      const bool half = 2 * R * KSr * groups <= kSkHalfTileMaxWorkgroups;
-      const int rc = dual ? (half ? launch_skinny_resident<true, true>(a, R, KSr, lds, st) : launch_skinny_resident<true, false>(a, R, KSr, lds, st))
-                          : (half ? launch_skinny_resident<false, true>(a, R, KSr, lds, st) : launch_skinny_resident<false, false>(a, R, KSr, lds, st));
-      if (rc != VNM_OK || KSr == 1) return rc;
-      return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
+    if (!lds) continue;
+    a.nsz = (int)nsz; a.z_stride = 0; a.tgroups = groups; a.R = R;
+    if (KSr > 1) {
+      a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
+      a.bias = nullptr; a.perm_out = nullptr;                             // applied by the reduction
     }
+    // one workgroup per 32-row tile while even those leave compute units idle
+    const bool half = rb == 1 && 2 * R * KSr * groups <= kSkHalfTileMaxWorkgroups;
+    int rc;
+    if (rb == 2) rc = dual ? launch_skinny_resident<true, false, 2>(a, R, KSr, lds, st) : launch_skinny_resident<false, false, 2>(a, R, KSr, lds, st);
+    else if (half) rc = dual ? launch_skinny_resident<true, true, 1>(a, R, KSr, lds, st) : launch_skinny_resident<false, true, 1>(a, R, KSr, lds, st);
+    else rc = dual ? launch_skinny_resident<true, false, 1>(a, R, KSr, lds, st) : launch_skinny_resident<false, false, 1>(a, R, KSr, lds, st);
+    if (rc != VNM_OK || KSr == 1) return rc;
+    return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
   }
   if (T > skinny_max_tokens()) return VNM_ERR_UNSUPPORTED;               // the phased kernel holds at most 32 token rows
   // steps per phase: a multiple of the 8 waves, at most 32, with at most kSkNX pieces of X per thread

@@ -250,6 +250,9 @@ RESIDENT_X_CASES = [
     (1024, 11008, 20, 64, 5),
     # 33 to 64 tokens while (row blocks x groups of 16 tokens) still fit the compute units at once
     (4096, 4096, 33, 64, 5), (4096, 4096, 64, 64, 5), (2080, 2048, 50, 32, 5), (2048, 4104, 64, 128, 8), (5000, 2048, 40, 64, 8),
+    # two row blocks per workgroup: more row blocks than fit one by one (even and odd count, two column tables),
+    # a slice of X that needs K split (4096 x 11008), and three token groups
+    (11008, 2048, 20, 64, 5), (8384, 2048, 32, 64, 5), (8352, 2080, 25, 32, 6), (4096, 11008, 32, 64, 5), (6000, 2048, 48, 64, 5),
 ]
 
 

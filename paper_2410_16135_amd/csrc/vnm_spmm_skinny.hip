@@ -33,6 +33,14 @@
 // 11.6 us on 4096 x 4096, 14.1 against 13.0 us on 11008 x 4096.  A ring of 13 operands (every weight
 // of a wave requested before X is complete) made it worse still: the weights crowd out the loads of X
 // that the barrier waits for.
+//
+// Also measured and dropped, on the 16-wave form of that kernel: the B operand of a step gathered once per
+// wave instead of once per lane (lane (token, K group) reads 8 halfwords of X and stores them as 16 bytes
+// of a wave-private strip [token][32 compacted K]; every lane reads its operand back with two 16-byte
+// reads: 11 LDS instructions and a dozen integer instructions per lane and step instead of 16 and about
+// 50).  Same results, slower: the store and the read-back are two more dependent LDS round trips per step
+// (device time per call at 16 tokens, weights from HBM: 4096 x 4096 10.8 against 9.6 us, 11008 x 4096 13.3
+// against 13.0; at 32 tokens 18.6 against 18.3 us on 11008 x 4096).
 #include "vnm_internal.h"
 
 namespace vnm {

@@ -213,7 +213,7 @@ int vnm::spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, co
     void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
     // a K range that fits LDS (or streams through it for few output channels) needs no staging pass:
     // one kernel straight from X
-    // up to 64 tokens on few row blocks: the few-token kernel, one workgroup per group of 16 tokens
+    // up to 128 tokens on few row blocks: the few-token kernel, one workgroup per group of 16 tokens
     if (!stage_perm && skinny_groups_applicable(T, d))
       return launch_spmm_skinny(Xk, T, ldk, packed, d, Y, ldy, y_dtype, nullptr, 0, f, st);
     if (!stage_perm && spmm_resident_applicable(T, d))

@@ -470,9 +470,9 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
   return VNM_OK;
 }
 
-// 33 to 64 tokens on few row blocks: groups of 16 tokens of the resident-X kernel, K unsplit (see the launcher)
+// 33 to 128 tokens on few row blocks: groups of 16 tokens of the resident-X kernel, K unsplit (see the launcher)
 bool skinny_groups_applicable(int64_t T, const Dims& d) {
-  if (T <= skinny_max_tokens() || T > 64 || !has_packed(d.V, d.M)) return false;
+  if (T <= skinny_max_tokens() || T > 128 || !has_packed(d.V, d.M)) return false;
   const int64_t groups = (T + 15) / 16;
   // one or two row blocks per workgroup (see the launcher), K unsplit
   return (packed_row_blocks(d) + 1) / 2 * groups <= kSkHalfTileMaxWorkgroups && d.S >= 32 && skinny_resident_lds(d.M, d.S) > 0;
@@ -498,7 +498,7 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
   // More than 16 tokens as groups of 16 of the resident-X kernel, one workgroup per (row block, group),
-  // where those workgroups still fit the compute units at once (the 4096-row layers up to 64 tokens: the
+  // where those workgroups still fit the compute units at once (the 4096-row layers up to 128 tokens: the
   // packed weight is then requested once per group and comes from HBM once; device time per call at
   // 64:2:5 on 4096 x 4096 at 32 tokens: 9.7 us against 14.6 us for the phased kernel)
   const int groups = (int)((T + 15) / 16);

@@ -253,6 +253,8 @@ RESIDENT_X_CASES = [
     # two row blocks per workgroup: more row blocks than fit one by one (even and odd count, two column tables),
     # a slice of X that needs K split (4096 x 11008), and three token groups
     (11008, 2048, 20, 64, 5), (8384, 2048, 32, 64, 5), (8352, 2080, 25, 32, 6), (4096, 11008, 32, 64, 5), (6000, 2048, 48, 64, 5),
+    # up to 128 tokens (eight groups) on at most 64 row blocks
+    (4096, 4096, 128, 64, 5), (4096, 4096, 100, 64, 5), (2080, 2048, 77, 32, 5), (1000, 4104, 128, 128, 8),
 ]
 
 

@@ -213,9 +213,9 @@ int vnm::spmm_impl(const void* X, int64_t T, int64_t ldx, const void* values, co
     void* scratch = scratch_bytes > 0 ? (char*)workspace + sb : nullptr;
     // a K range that fits LDS (or streams through it for few output channels) needs no staging pass:
     // one kernel straight from X
-    // up to 128 tokens on few row blocks: the few-token kernel, one workgroup per group of 16 tokens
-    if (!stage_perm && skinny_groups_applicable(T, d))
-      return launch_spmm_skinny(Xk, T, ldk, packed, d, Y, ldy, y_dtype, nullptr, 0, f, st);
+    // up to 256 tokens where its workgroups fit the compute units at once: the few-token kernel in token groups
+    if (!stage_perm && skinny_groups_applicable(T, d, scratch_bytes))
+      return launch_spmm_skinny(Xk, T, ldk, packed, d, Y, ldy, y_dtype, scratch, scratch_bytes, f, st);
     if (!stage_perm && spmm_resident_applicable(T, d))
       return launch_spmm_resident(Xk, T, ldk, packed, d, Y, ldy, y_dtype, f, st);
     rc = launch_stage_x(Xk, T, ldk, d, stage_perm, workspace, st);
@@ -311,7 +311,8 @@ extern "C" int vnm_spmm_kernel_choice(int64_t T, int64_t out, int64_t in, int V,
   const Dims d = make_dims(out, in, V, M);
   *choice = VNM_KERNEL_GENERIC;
   if (!has_packed(V, M) || in % 8 != 0) return VNM_OK;
-  if (T <= skinny_max_tokens() || skinny_groups_applicable(T, d)) { *choice = VNM_KERNEL_FEW_TOKENS; return VNM_OK; }
+  // (with the workspace vnm_spmm_workspace_bytes asks for)
+  if (T <= skinny_max_tokens() || skinny_groups_applicable(T, d, splitk_scratch_bytes(T, out))) { *choice = VNM_KERNEL_FEW_TOKENS; return VNM_OK; }
   *choice = spmm_resident_applicable(T, d) ? VNM_KERNEL_RESIDENT : VNM_KERNEL_STAGED;
   return VNM_OK;
 }

@@ -127,8 +127,9 @@ int launch_lora_merge(const void* W, int64_t ldw, const void* B, int64_t ldb, co
                       float scale, int64_t out, int64_t in, void* Wm, int64_t ldm, hipStream_t st);
 // Single-kernel product for at most skinny_max_tokens() tokens, straight from X (no staging, no workspace).
 int64_t skinny_max_tokens();
-// The same kernels also serve up to 128 tokens on matrices with few row blocks (no staging, no workspace use).
-bool skinny_groups_applicable(int64_t T, const Dims& d);
+// The same kernels also serve up to 256 tokens where their workgroups fit the compute units at once (no
+// staging; scratch_bytes: what the caller can offer for split-K partial products).
+bool skinny_groups_applicable(int64_t T, const Dims& d, int64_t scratch_bytes);
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
                        void* Y, int64_t ldy, int y_dtype, void* scratch, int64_t scratch_bytes,
                        const Fused& f, hipStream_t st);

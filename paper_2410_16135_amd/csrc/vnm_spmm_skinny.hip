@@ -251,9 +251,9 @@ constexpr int kSkNXR = 10;       // 16-byte pieces of X per thread, at most (16 
 // HALF: one workgroup per 32-row tile (blockIdx.z picks the tile of the 64-row block) instead of one per
 // block -- twice the workgroups where a matrix has too few row blocks to occupy the compute units; each
 // fetches the whole slice of X but only its tile's weights.
-template <bool DUAL, bool HALF, int RB>
+template <bool DUAL, bool HALF, int RB, int TT>
 __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(const SkinnyArgs a) {
-  constexpr int AT = 2, TT = 16;
+  constexpr int AT = 2;
   constexpr int NT = HALF ? 1 : AT;                  // tiles of this workgroup
   const int t0 = HALF ? (int)blockIdx.z : 0;         // its first tile
   // operands requested ahead per wave (see the table above)
@@ -269,11 +269,11 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
   const int64_t r = r_own < a.R ? r_own : a.R - 1;
   const int M = a.M;
   const int64_t S = a.S;
-  // blockIdx.y = K piece * token groups + token group; a group is 16 token rows of X and Y
+  // blockIdx.y = K piece * token groups + token group; a group is TT token rows of X and Y
   const int tg = (int)(blockIdx.y % (unsigned)a.tgroups);
   const int64_t ky = blockIdx.y / (unsigned)a.tgroups;
-  const int64_t Tg = a.T - 16 * tg < 16 ? a.T - 16 * tg : 16;       // tokens of this group (at least one)
-  const unsigned short* Xg = a.X + (int64_t)tg * 16 * a.ldx;
+  const int64_t Tg = a.T - TT * tg < TT ? a.T - TT * tg : TT;       // tokens of this group (at least one)
+  const unsigned short* Xg = a.X + (int64_t)tg * TT * a.ldx;
   const int64_t s_lo = ky * a.nsz;
   const int64_t s_hi = s_lo + a.nsz < S ? s_lo + a.nsz : S;
   const int ncol = a.nsz * 8 * M;                    // raw columns of a workgroup's K range
@@ -295,8 +295,8 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
 
   // X slice -> LDS, [token][raw column], in 16-byte pieces.  One wave-wide load takes a block of 4 token
   // rows x 16 chunks (256-byte runs of a row: whole cache lines; in LDS the four rows start an odd number
-  // of dwords apart, so the 64 lanes' stores fall into 64 different banks); block number wave + 16 i is
-  // (token group b & 3, chunk group b >> 2).  Rows beyond T and columns beyond `in` become zero.  The
+  // of dwords apart, so the 64 lanes' stores fall into 64 different banks); block number b = wave + 16 i is
+  // (group of 4 token rows b % (TT / 4), chunk group b / (TT / 4)).  Rows beyond T and columns beyond `in` become zero.  The
   // first ring of weight operands is requested right after X: loads return in order, so X (from L2) is
   // not held up behind the weights (from HBM), and the weights travel while X is being parked in LDS.
   {
@@ -304,15 +304,16 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
     const int c_lo = lane & 15, rsub = lane >> 4;
     constexpr int NB = DUAL ? 2 : 1;                 // one batch where the registers allow it
     constexpr int HB = kSkNXR / NB;
-    // All blocks of a thread lie in one token row ((wave + 16 k) & 3 = wave & 3), 512 columns apart:
+    // All blocks of a thread lie in one token row (16 is a multiple of TT / 4), CG * 128 columns apart:
     // one row pointer (a valid row also for tokens beyond T) and a 32-bit column, clamped to the last
     // 8 columns that exist in the K range and in the row -- what a clamped load brings is dropped below.
-    const int x_tok = (wave & 3) * 4 + rsub;
+    constexpr int NG = TT / 4;                       // groups of 4 token rows
+    const int x_tok = (wave % NG) * 4 + rsub;
     const unsigned short* x_row = Xg + (x_tok < Tg ? x_tok * a.ldx : 0);
     const int64_t span_end = col0 + ncol;
     const unsigned col_last = (unsigned)((span_end < a.in ? span_end : a.in) - 8);
-    const unsigned col_first = (unsigned)col0 + (unsigned)(((wave >> 2) * 16 + c_lo) * 8);
-    constexpr int CG = kSkWavesR / 4;               // chunk groups of 16 pieces taken per round of wave-wide loads
+    const unsigned col_first = (unsigned)col0 + (unsigned)(((wave / NG) * 16 + c_lo) * 8);
+    constexpr int CG = kSkWavesR / NG;              // chunk groups of 16 pieces taken per round of wave-wide loads
 #pragma unroll
     for (int half = 0; half < NB; ++half) {
       uint4 xw[HB];
@@ -329,7 +330,7 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i) {
-        const int tok = x_tok, ch = ((wave >> 2) + CG * (half * HB + i)) * 16 + c_lo;
+        const int tok = x_tok, ch = ((wave / NG) + CG * (half * HB + i)) * 16 + c_lo;
         if (ch < CH) {
           const bool ok = tok < Tg && col0 + ch * 8 < a.in;
           const uint4 v = ok ? xw[i] : make_uint4(0, 0, 0, 0);
@@ -347,7 +348,7 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
 #pragma unroll
     for (int k = 0; k < 16; ++k) acc[t][k] = 0.f;
 
-  const int tokl = lane & 15;                        // lanes 16..31 repeat tokens 0..15
+  const int tokl = lane & (TT - 1);                  // TT = 16: lanes 16..31 repeat tokens 0..15
   auto compute = [&](const AOp& o, int64_t s) {
     const unsigned char* row = smem + (size_t)tokl * pitch + (size_t)(s - s_lo) * 16 * M;
     unsigned pc[2][4];
@@ -426,32 +427,86 @@ __global__ void __launch_bounds__(64 * kSkWavesR) spmm_skinny_resident_kernel(co
       if (a.bias) sum += (float)a.bias[o];
       const int64_t dst = a.perm_out ? (int64_t)a.perm_out[o] : o;          // Eq. 6, P_o^T
       if (dst < 0 || dst >= a.out) continue;
-      const int64_t yrow = 16 * tg + tok;
+      const int64_t yrow = TT * tg + tok;
       if (a.y_fp32) ((float*)a.Y)[ky * a.z_stride + yrow * a.ldy + dst] = sum;
       else ((_Float16*)a.Y)[yrow * a.ldy + dst] = (_Float16)sum;
     }
   }
 }
 
-// LDS of the resident-X kernel for nsz K steps per workgroup; 0 if they do not fit
-static size_t skinny_resident_lds(int M, int64_t nsz) {
-  const size_t x = (size_t)16 * ((size_t)nsz * 16 * M + 4);
-  const size_t red = (size_t)kSkWavesR * 16 * (2 * 32 + 1) * 4;
+// LDS of the resident-X kernel for nsz K steps and tt token rows per workgroup; 0 if they do not fit
+static size_t skinny_resident_lds(int M, int64_t nsz, int tt) {
+  const size_t x = (size_t)tt * ((size_t)nsz * 16 * M + 4);
+  const size_t red = (size_t)kSkWavesR * tt * (2 * 32 + 1) * 4;
   const size_t lds = x > red ? x : red;
-  // kSkNXR wave-wide loads per wave cover the slice: 4 token groups x ceil(nsz M / 16) chunk groups
-  if (lds > 150 * 1024 || 4 * (((size_t)nsz * M + 15) / 16) > (size_t)kSkWavesR * kSkNXR) return 0;
+  // kSkNXR wave-wide loads per wave cover the slice: tt / 4 groups of token rows x ceil(nsz M / 16) chunk groups
+  if (lds > 150 * 1024 || (size_t)(tt / 4) * (((size_t)nsz * M + 15) / 16) > (size_t)kSkWavesR * kSkNXR) return 0;
   return lds;
 }
 
-template <bool DUAL, bool HALF, int RB>
+template <bool DUAL, bool HALF, int RB, int TT>
 static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t lds, hipStream_t st) {
-  auto kern = spmm_skinny_resident_kernel<DUAL, HALF, RB>;
+  auto kern = spmm_skinny_resident_kernel<DUAL, HALF, RB, TT>;
   if (int rc_lds = allow_big_lds((const void*)kern, "hipFuncSetAttribute(spmm_skinny_resident)")) return rc_lds;
   hipLaunchKernelGGL(kern, dim3((unsigned)((R + RB - 1) / RB), (unsigned)(KS * a.tgroups), HALF ? 2u : 1u),
                      dim3(64 * kSkWavesR), lds, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error(e, "spmm_skinny_resident_kernel"); return VNM_ERR_HIP; }
   return VNM_OK;
+}
+
+// How the resident-X kernel serves T tokens, if it can.
+//   tt      token rows per workgroup: 16, or 32 where groups of 16 would not fit (a group of 32 costs a
+//           workgroup the same instructions per K step and twice the slice of X)
+//   rb      row blocks per workgroup (the waves are dealt out to them; one slice of X for all)
+//   ks      workgroups along K (> 1: fp32 partial products in the scratch, summed by splitk_reduce)
+// All (row, K, token-group) workgroups must fit the compute units at once: one whose turn comes later
+// starts from nothing when the first ones end.  Tried in this order: 16 tokens and one row block per
+// workgroup; 16 tokens and two row blocks; 32 tokens and one, two or four row blocks with K split as far
+// as the slice of X needs.
+struct SkPlan { int tt, rb, groups; int64_t ks, nsz; size_t lds; bool half; };
+
+static bool skinny_plan(int64_t T, const Dims& d, bool have_scratch, int64_t scratch_bytes, SkPlan* p) {
+  const int64_t R = packed_row_blocks(d);
+  const int tts[2] = {16, 32};
+  for (int ti = 0; ti < (T > 16 ? 2 : 1); ++ti) {
+    const int tt = tts[ti];
+    const int groups = (int)((T + tt - 1) / tt);
+    const int rb_max = groups == 1 ? 1 : (tt == 16 ? 2 : 4);
+    for (int rb = 1; rb <= rb_max; rb *= 2) {
+      const int64_t Re = (R + rb - 1) / rb;                               // workgroups along the rows
+      if (T > 16 && Re * groups > kSkHalfTileMaxWorkgroups) continue;
+      int64_t ks = 1;
+      if (tt == 16) {
+        // K is split (while the workgroups still fit the 256 CUs at once) only beyond 128 K steps, into
+        // pieces of at least 32: a shorter K is done sooner by one workgroup per row block than by
+        // several plus the reduction launch (measured at 64:2:5 and 64:2:8 on 4096 x 4096: 12.6 / 10.7 us
+        // unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split in four against
+        // 18.1 us split in two)
+        if (have_scratch && T <= skinny_max_tokens() && Re * groups <= 128 && d.S > 128) {
+          ks = 256 / (Re * groups);
+          if (ks > 16) ks = 16;
+          if (ks > d.S / 32) ks = d.S / 32;
+        }
+      } else {
+        // 32 tokens per workgroup: as few pieces of K as the slice of X allows
+        while (ks <= 8 && (d.S + ks - 1) / ks >= 32 && !skinny_resident_lds(d.M, (d.S + ks - 1) / ks, tt)) ++ks;
+        if (ks > 1 && !have_scratch) continue;
+        if (Re * groups * ks > kSkHalfTileMaxWorkgroups) continue;
+      }
+      while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
+      const int64_t nsz = (d.S + ks - 1) / ks;
+      // below 32 steps per workgroup there is nothing to keep in flight
+      const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz, tt) : 0;
+      if (!lds) continue;
+      const int64_t KSr = (d.S + nsz - 1) / nsz;
+      p->tt = tt; p->rb = rb; p->groups = groups; p->ks = KSr; p->nsz = nsz; p->lds = lds;
+      // one workgroup per 32-row tile while even those leave compute units idle
+      p->half = tt == 16 && rb == 1 && 2 * R * KSr * groups <= kSkHalfTileMaxWorkgroups;
+      return true;
+    }
+  }
+  return false;
 }
 
 int64_t skinny_max_tokens() { return 32; }
@@ -470,12 +525,12 @@ static int launch_skinny_cfg(const SkinnyArgs& a, int64_t R, int KS, hipStream_t
   return VNM_OK;
 }
 
-// 33 to 128 tokens on few row blocks: groups of 16 tokens of the resident-X kernel, K unsplit (see the launcher)
-bool skinny_groups_applicable(int64_t T, const Dims& d) {
-  if (T <= skinny_max_tokens() || T > 128 || !has_packed(d.V, d.M)) return false;
-  const int64_t groups = (T + 15) / 16;
-  // one or two row blocks per workgroup (see the launcher), K unsplit
-  return (packed_row_blocks(d) + 1) / 2 * groups <= kSkHalfTileMaxWorkgroups && d.S >= 32 && skinny_resident_lds(d.M, d.S) > 0;
+// 33 to 256 tokens where the resident-X kernel can take them in groups (see skinny_plan); scratch_bytes:
+// what the caller can offer for split-K partial products
+bool skinny_groups_applicable(int64_t T, const Dims& d, int64_t scratch_bytes) {
+  if (T <= skinny_max_tokens() || T > 256 || !has_packed(d.V, d.M)) return false;
+  SkPlan p;
+  return skinny_plan(T, d, scratch_bytes > 0, scratch_bytes, &p);
 }
 
 int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed, const Dims& d,
@@ -497,45 +552,30 @@ int launch_spmm_skinny(const void* X, int64_t T, int64_t ldx, const void* packed
   a.Y = Y; a.ldy = ldy; a.y_fp32 = y_dtype;
   a.bias = f.bias; a.perm_out = f.perm_out;
   const int TT = T <= 16 ? 16 : 32;
-  // More than 16 tokens as groups of 16 of the resident-X kernel, one workgroup per (row block, group),
-  // where those workgroups still fit the compute units at once (the 4096-row layers up to 128 tokens: the
-  // packed weight is then requested once per group and comes from HBM once; device time per call at
+  // the resident-X kernel where it applies (T <= 16, or more tokens in groups of 16 or 32 per workgroup:
+  // the packed weight is then requested once per group and comes from HBM once; device time per call at
   // 64:2:5 on 4096 x 4096 at 32 tokens: 9.7 us against 14.6 us for the phased kernel)
-  const int groups = (int)((T + 15) / 16);
-  if (T > skinny_max_tokens() && !skinny_groups_applicable(T, d)) return VNM_ERR_UNSUPPORTED;
-  // resident-X kernel.  K is split over workgroups (with scratch, while they all still fit the 256 CUs at
-  // once) only beyond 128 K steps, into pieces of at least 32: a shorter K is done sooner by one
-  // workgroup per row block than by several plus the reduction launch (measured at 64:2:5 and 64:2:8 on
-  // 4096 x 4096: 12.6 / 10.7 us unsplit against 13.5 / 12.7 us split in four; 4096 x 11008: 15.2 us split
-  // in four against 18.1 us split in two).  With several token groups, a workgroup takes two row blocks
-  // (8 waves each, one slice of X for both) where one per workgroup would not fit the compute units at
-  // once or would need a slice of X larger than LDS.
-  for (int rb = 1; rb <= (groups > 1 ? 2 : 1); ++rb) {
-    const int64_t Re = (R + rb - 1) / rb;                                 // workgroups along the rows
-    if (T > 16 && Re * groups > kSkHalfTileMaxWorkgroups) continue;
-    int64_t ks = 1;
-    if (scratch && T <= skinny_max_tokens() && Re * groups <= 128 && d.S > 128) {
-      ks = 256 / (Re * groups);
-      if (ks > 16) ks = 16;
-      if (ks > d.S / 32) ks = d.S / 32;
-      while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
-    }
-    const int64_t nsz = (d.S + ks - 1) / ks;
-    const int KSr = (int)((d.S + nsz - 1) / nsz);
-    // below 32 steps per workgroup (4 per wave) there is nothing to keep in flight: the phased kernel
-    const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz) : 0;
-    if (!lds) continue;
-    a.nsz = (int)nsz; a.z_stride = 0; a.tgroups = groups; a.R = R;
+  SkPlan pl2;
+  if (skinny_plan(T, d, scratch != nullptr, scratch_bytes, &pl2)) {
+    a.nsz = (int)pl2.nsz; a.z_stride = 0; a.tgroups = pl2.groups; a.R = R;
+    const int KSr = (int)pl2.ks;
     if (KSr > 1) {
       a.Y = scratch; a.ldy = d.out; a.y_fp32 = 1; a.z_stride = T * d.out;
       a.bias = nullptr; a.perm_out = nullptr;                             // applied by the reduction
     }
-    // one workgroup per 32-row tile while even those leave compute units idle
-    const bool half = rb == 1 && 2 * R * KSr * groups <= kSkHalfTileMaxWorkgroups;
-    int rc;
-    if (rb == 2) rc = dual ? launch_skinny_resident<true, false, 2>(a, R, KSr, lds, st) : launch_skinny_resident<false, false, 2>(a, R, KSr, lds, st);
-    else if (half) rc = dual ? launch_skinny_resident<true, true, 1>(a, R, KSr, lds, st) : launch_skinny_resident<false, true, 1>(a, R, KSr, lds, st);
-    else rc = dual ? launch_skinny_resident<true, false, 1>(a, R, KSr, lds, st) : launch_skinny_resident<false, false, 1>(a, R, KSr, lds, st);
+    int rc = VNM_ERR_UNSUPPORTED;
+#define VNM_SK_LAUNCH(H, RBV, TTV) \
+    rc = dual ? launch_skinny_resident<true, H, RBV, TTV>(a, R, KSr, pl2.lds, st) : launch_skinny_resident<false, H, RBV, TTV>(a, R, KSr, pl2.lds, st)
+    if (pl2.tt == 16) {
+      if (pl2.rb == 2) VNM_SK_LAUNCH(false, 2, 16);
+      else if (pl2.half) VNM_SK_LAUNCH(true, 1, 16);
+      else VNM_SK_LAUNCH(false, 1, 16);
+    } else {
+      if (pl2.rb == 4) VNM_SK_LAUNCH(false, 4, 32);
+      else if (pl2.rb == 2) VNM_SK_LAUNCH(false, 2, 32);
+      else VNM_SK_LAUNCH(false, 1, 32);
+    }
+#undef VNM_SK_LAUNCH
     if (rc != VNM_OK || KSr == 1) return rc;
     return launch_splitk_reduce(scratch, KSr, T, d.out, Y, ldy, y_dtype, f, st);
   }

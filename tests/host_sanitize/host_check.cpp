@@ -41,7 +41,7 @@ bool prune_fast_applicable(const void*, int64_t, const Dims&, const void*) { ret
 bool prune_fast_scored_applicable(const void*, int64_t, const void*, int64_t, const Dims&) { return true; }
 bool decompress_fast_applicable(const void*, int64_t, const Dims&) { return true; }
 bool spmm_resident_applicable(int64_t, const Dims&) { return false; }
-bool skinny_groups_applicable(int64_t, const Dims&) { return false; }
+bool skinny_groups_applicable(int64_t, const Dims&, int64_t) { return false; }
 bool spmm_smfmac_applicable(const void* X, int64_t ldx, const Dims& d) {
   return has_packed(d.V, d.M) && d.in % 8 == 0 && ldx % 8 == 0 && ((uintptr_t)X & 15) == 0;
 }

@@ -39,7 +39,7 @@ FUSED_CASES = [
     (64, 640, 257, 64, 16), (384, 384, 520, 64, 5), (512, 2048, 100, 64, 5), (1024, 1280, 40, 64, 8),
     (130, 96, 300, 64, 7), (2048, 512, 24, 64, 5),
     # at most 16 tokens, X resident in LDS: epilogue in the kernel (unsplit) and in the reduction (split K)
-    (8256, 1320, 12, 64, 5), (4096, 5600, 16, 64, 5), (1024, 2048, 24, 64, 5), (512, 5600, 29, 64, 5), (1024, 2048, 47, 64, 5), (8384, 1320, 30, 64, 5), (1024, 2048, 90, 64, 5),
+    (8256, 1320, 12, 64, 5), (4096, 5600, 16, 64, 5), (1024, 2048, 24, 64, 5), (512, 5600, 29, 64, 5), (1024, 2048, 47, 64, 5), (8384, 1320, 30, 64, 5), (1024, 2048, 90, 64, 5), (4096, 2048, 200, 64, 5), (4096, 4096, 192, 64, 5),
     # one to four tokens, the product on the vector ALUs: 16 waves per tile, 8 waves (more tiles than compute
     # units), two column tables
     (1024, 1280, 1, 64, 5), (8320, 1320, 2, 64, 5), (352, 2048, 4, 32, 8),

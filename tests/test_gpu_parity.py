@@ -255,6 +255,11 @@ RESIDENT_X_CASES = [
     (11008, 2048, 20, 64, 5), (8384, 2048, 32, 64, 5), (8352, 2080, 25, 32, 6), (4096, 11008, 32, 64, 5), (6000, 2048, 48, 64, 5),
     # up to 128 tokens (eight groups) on at most 64 row blocks
     (4096, 4096, 128, 64, 5), (4096, 4096, 100, 64, 5), (2080, 2048, 77, 32, 5), (1000, 4104, 128, 128, 8),
+    # groups of 32 tokens per workgroup where groups of 16 would not fit the compute units: four row blocks per
+    # workgroup with K split in two (192 and 256 tokens on 64 row blocks; 64 tokens on 172 row blocks; two column
+    # tables), two row blocks unsplit, and many groups of 16 on very few row blocks
+    (4096, 4096, 192, 64, 5), (4096, 4096, 256, 64, 5), (11008, 4096, 64, 64, 5), (4160, 4096, 200, 32, 6),
+    (4096, 2048, 200, 64, 5), (1024, 2048, 250, 64, 5),
 ]
 
 

@@ -461,19 +461,22 @@ static int launch_skinny_resident(const SkinnyArgs& a, int64_t R, int KS, size_t
 //   rb      row blocks per workgroup (the waves are dealt out to them; one slice of X for all)
 //   ks      workgroups along K (> 1: fp32 partial products in the scratch, summed by splitk_reduce)
 // All (row, K, token-group) workgroups must fit the compute units at once: one whose turn comes later
-// starts from nothing when the first ones end.  Tried in this order: 16 tokens and one row block per
-// workgroup; 16 tokens and two row blocks; 32 tokens and one, two or four row blocks with K split as far
-// as the slice of X needs.
+// starts from nothing when the first ones end.  Candidates: 16 tokens and one or two row blocks per
+// workgroup; 32 tokens and one, two or four row blocks with K split as far as the slice of X needs.
 struct SkPlan { int tt, rb, groups; int64_t ks, nsz; size_t lds; bool half; };
 
 static bool skinny_plan(int64_t T, const Dims& d, bool have_scratch, int64_t scratch_bytes, SkPlan* p) {
   const int64_t R = packed_row_blocks(d);
-  const int tts[2] = {16, 32};
-  for (int ti = 0; ti < (T > 16 ? 2 : 1); ++ti) {
-    const int tt = tts[ti];
+  // candidates (tokens per workgroup, smallest and largest number of row blocks per workgroup), in the order
+  // they are tried.  Up to 32 tokens one group of 32 comes before two groups of 16 with two row blocks each
+  // (11008 x 4096 at 32 tokens: 16.9 against 18.5 us); beyond, the groups of 16 come first (4096 x 4096 at 128
+  // tokens: 15.4 us against 16.6 us for groups of 32 with K in two pieces).
+  const int cand[4][3] = {{16, 1, 1}, {T <= 32 ? 32 : 16, T <= 32 ? 1 : 2, T <= 32 ? 4 : 2}, {16, 2, 2}, {32, 1, 4}};
+  for (int ci = 0; ci < (T > 16 ? 4 : 1); ++ci) {
+    const int tt = cand[ci][0];
     const int groups = (int)((T + tt - 1) / tt);
-    const int rb_max = groups == 1 ? 1 : (tt == 16 ? 2 : 4);
-    for (int rb = 1; rb <= rb_max; rb *= 2) {
+    if (tt == 16 && groups == 1 && cand[ci][1] > 1) continue;
+    for (int rb = cand[ci][1]; rb <= cand[ci][2]; rb *= 2) {
       const int64_t Re = (R + rb - 1) / rb;                               // workgroups along the rows
       if (T > 16 && Re * groups > kSkHalfTileMaxWorkgroups) continue;
       int64_t ks = 1;

@@ -154,8 +154,10 @@ int vnm_pack(const void* values, const void* meta, const void* colidx,
  * The matrix-core kernel needs V in {32, 64, 128}, M <= 16, in % 8 == 0, ldx % 8 == 0 and X 16-byte
  * aligned; otherwise (or when `packed` is NULL) AUTO uses the generic kernel, which needs no
  * workspace.  For T <= 32 the matrix-core path is a single kernel that reads X directly and needs no
- * workspace (if one is given, its scratch part may hold split-K partial products).  For larger T, when the matrix-core kernel applies but the workspace is missing or too
- * small the call fails with VNM_ERR_WORKSPACE instead of silently taking the slow kernel.
+ * workspace (if one is given, its scratch part may hold split-K partial products).  For larger T, when the
+ * matrix-core kernel applies but the workspace is missing or too small the call fails with VNM_ERR_WORKSPACE
+ * instead of silently taking the slow kernel (also where, up to 256 tokens, the few-token kernels end up
+ * serving the call and use at most the scratch part).
  * T == 0 is a successful no-op (X and Y may then be NULL).
  */
 int vnm_spmm(const void* X, int64_t T, int64_t ldx,
@@ -257,7 +259,10 @@ int vnm_spmm_scratch_bytes(int64_t T, int64_t out, int64_t* bytes);
  * Host only.  Which kernel vnm_spmm (VNM_PATH_AUTO, `packed` given, X aligned as the matrix-core
  * kernels need it, no input permutation) runs for T tokens with a workspace of the given size:
  *   VNM_KERNEL_GENERIC     scalar kernel (no matrix-core copy for this V, M, or in % 8 != 0)
- *   VNM_KERNEL_FEW_TOKENS  T <= 32: one kernel, X token-major in LDS
+ *   VNM_KERNEL_FEW_TOKENS  no staging pass, X token-major in LDS (one to four tokens: a stream through the vector
+ *                          ALUs): T <= 32 always; up to 256 tokens where one workgroup per (row blocks, group of 16
+ *                          or 32 tokens, piece of K) fits the compute units at once (with the workspace that
+ *                          vnm_spmm_workspace_bytes asks for; fp32 partial products + a reduction kernel if K is split)
  *   VNM_KERNEL_RESIDENT    one kernel without a staging pass: the workgroup's slice of X is turned
  *                          around into LDS by the kernel itself (a K range that fits LDS; or at most
  *                          1024 output channels and at least 8192 tokens, K streaming through LDS)

@@ -1,5 +1,6 @@
-// vnm_spmm for at most 32 tokens (decode, small batches): one kernel, no staging pass; a workspace is
-// optional (split K for few row blocks, see the launcher).
+// vnm_spmm for few tokens (decode, small batches): no staging pass; at most 32 tokens always (a workspace
+// is optional then: split K for few row blocks), up to 256 tokens where the resident-X kernel further down
+// can take them in groups (skinny_plan).
 //
 // With so few tokens the product is a stream of the compressed weight through the matrix cores at
 // HBM rate; what matters is that every byte of it is requested early and read once.  One workgroup

@@ -492,6 +492,11 @@ static bool skinny_plan(int64_t T, const Dims& d, bool have_scratch, int64_t scr
           if (ks > 16) ks = 16;
           if (ks > d.S / 32) ks = d.S / 32;
         }
+        // a slice of X that does not fit LDS (wide blocks, M = 16: 16 tokens x 32 M bytes per K step):
+        // more pieces, down to 16 K steps each, while the workgroups still fit the compute units
+        if (have_scratch && T <= skinny_max_tokens())
+          while (ks < 16 && (d.S + ks - 1) / ks >= 16 && !skinny_resident_lds(d.M, (d.S + ks - 1) / ks, tt) &&
+                 Re * groups * (ks + 1) <= kSkHalfTileMaxWorkgroups) ++ks;
       } else {
         // 32 tokens per workgroup: as few pieces of K as the slice of X allows
         while (ks <= 8 && (d.S + ks - 1) / ks >= 32 && !skinny_resident_lds(d.M, (d.S + ks - 1) / ks, tt)) ++ks;
@@ -500,8 +505,8 @@ static bool skinny_plan(int64_t T, const Dims& d, bool have_scratch, int64_t scr
       }
       while (ks > 1 && ks * T * d.out * 4 > scratch_bytes) --ks;
       const int64_t nsz = (d.S + ks - 1) / ks;
-      // below 32 steps per workgroup there is nothing to keep in flight
-      const size_t lds = nsz >= 32 ? skinny_resident_lds(d.M, nsz, tt) : 0;
+      // below 32 steps per workgroup (16 where K had to be split for LDS) there is nothing to keep in flight
+      const size_t lds = nsz >= (ks > 1 ? 16 : 32) ? skinny_resident_lds(d.M, nsz, tt) : 0;
       if (!lds) continue;
       const int64_t KSr = (d.S + nsz - 1) / nsz;
       p->tt = tt; p->rb = rb; p->groups = groups; p->ks = KSr; p->nsz = nsz; p->lds = lds;

@@ -513,7 +513,8 @@ def main():
     # more host time (about 11 us) than its kernel takes, so the per-call events above time the host; a
     # graph of the pass -- how a serving loop would issue it -- times the device.  Both sides the same way.
     graph_replay = None
-    if layers[0].tokens <= 32 and not args.no_graph:
+    all_few = all(choice[L.name] == vnm.KERNEL_FEW_TOKENS for L in layers)     # every layer runs a few-token kernel
+    if all_few and not args.no_graph:
         def replay_ms(fn):
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
@@ -645,14 +646,14 @@ def main():
         "calibration_copy": {"bytes_read": calib_bytes, "bytes_written": calib_bytes,
                              "what": "one torch copy_ of the first layer's W after the timed region"},
     }
-    if L0.tokens <= 32:
+    if all_few:
         # few tokens: the product is a stream of the packed weight, bound by HBM, not by the matrix cores
         packed_bytes = float(sum(c.packed.numel() for (_, _, _, c, _, _) in state))
         result["roofline"] = {
             "bound": "hbm",
             "kernel": ("spmm_gemv_kernel (vector ALUs; three and four tokens on 4096 x 11008: the matrix-core few-token kernel)"
                        if L0.tokens <= 4 else
-                       "spmm_skinny_kernel / spmm_skinny_resident_kernel (+ splitk_reduce_kernel)"),
+                       "spmm_skinny_resident_kernel / spmm_skinny_kernel (+ splitk_reduce_kernel)"),
             "achieved": packed_bytes / product_in_step_ms / 1e6, "peak": 8000.0, "unit": "GB/s",
             "frac": packed_bytes / product_in_step_ms / 1e6 / 8000.0, "traffic": None,
             "launches_per_step": len(layers), "avg_launch_us": product_in_step_ms / len(layers) * 1e3,

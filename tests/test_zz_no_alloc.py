@@ -52,6 +52,14 @@ def test_noalloc_matches_vnm_spmm_two_calls_in_a_row(y_dtype):
     _pair(256, 640, 128, 6, 1000, seed=14, y_dtype=y_dtype)
 
 
+def test_noalloc_token_groups_of_the_few_token_kernel():
+    # 33 to 256 tokens served by the few-token kernel in token groups (no staging; the array holds split-K
+    # partial products at most), unsplit and with K split, then a smaller input
+    _pair(2048, 2048, 64, 5, 100, seed=17, y_dtype=torch.float16)
+    _pair(1024, 11008, 64, 5, 24, seed=18, y_dtype=torch.float32)
+    _pair(512, 2048, 32, 6, 7, seed=19, y_dtype=torch.float16)
+
+
 def test_noalloc_bit_equal_where_the_split_is_the_same():
     # above 2048 tokens nothing is split: the two entry points run the same kernels on the same data
     got, ref = _pair(128, 256, 64, 8, 2500, seed=15, y_dtype=torch.float16)

@@ -58,6 +58,23 @@ def test_prune_spmm_decompress_repeat_bit_for_bit(name, tokens):
 
 
 @pytest.mark.parametrize("name", ["q", "gate", "down"])
+def test_few_token_products_repeat_bit_for_bit(name):
+    """One to 256 tokens at the full layer sizes: the vector-ALU kernel, the resident-X kernel alone, in token
+    groups, with several row blocks per workgroup and with K split -- every call must return the same bits (the
+    sums through LDS and the split-K reduction run in a fixed order; wave-private LDS strips are written and read
+    back without a barrier)."""
+    layer, Wd, Xd = _layer(name, 256)
+    c = vnm.vnm_prune_compress(Wd, layer.V, layer.M)
+    for T in (1, 2, 4, 7, 16, 24, 32, 48, 64, 100, 192, 256):
+        X = Xd[:T].contiguous()
+        first = vnm.vnm_spmm(X, c)
+        for _ in range(4):
+            again = vnm.vnm_spmm(X, c)
+            torch.cuda.synchronize()
+            assert _same(first, again), T
+
+
+@pytest.mark.parametrize("name", ["q", "gate", "down"])
 def test_scores_search_kernels_and_merge_repeat_bit_for_bit(name):
     layer, Wd, Xd = _layer(name, 64)
     act = Xd.float().pow(2).sum(dim=0).sqrt().pow(0.5).contiguous()
